@@ -1,0 +1,130 @@
+/*
+ * libconvrot - ConvLinear4bit forward path for AMD MI355X (gfx950).
+ *
+ * C ABI.  The path is the one layer the ConvRot paper (arXiv 2512.03673, Sec. 4.3) calls
+ * ConvLinear4bit:  Y = X W^T  computed as
+ *
+ *   X' = R_g(X)                      group-wise regular-Hadamard rotation        (Sec. 4.2, Eq. 11-13)
+ *   q_x, s_x = Q4(X') per token      symmetric 4-bit codes, one scale per row    (Eq. 1, Sec. 5.2)
+ *   acc = q_x q_w^T                  integer GEMM on the codes                   (Sec. 4.3)
+ *   Y = bf16(acc * s_x[m] * s_w[n])  dequantisation                              (Sec. 4.3, suppl. Sec. B)
+ *
+ * with (q_w, s_w) = Q4(R_g(W)) prepared once, offline, per output channel (Eq. 12-13, Sec. 5.2).
+ * R_g applies H_g / sqrt(g) to every length-g block of every row, H_g being the Kronecker power
+ * of the order-4 regular Hadamard matrix of Thm 3.3 / Eq. 9; g (the paper's N_0) is 4, 16, 64,
+ * 256 or 1024.
+ *
+ * Conventions for every entry point
+ *   - Pointers named in the comments as DEVICE are device (HBM) pointers; everything else is
+ *     passed by value.  All matrices are row-major and contiguous.  bf16 is the raw 16-bit
+ *     pattern.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Calls are asynchronous on `stream`; they allocate and free nothing and keep no state.
+ *     The caller owns every buffer, including the workspace, for the duration of the work.
+ *   - Inputs are never written.  Outputs must not alias inputs.
+ *   - Return value: CONVROT_OK (0) or a negative convrot_status.  Arguments are validated on
+ *     the host before any launch: on an argument error nothing is launched and no output byte
+ *     is written.  The library never throws or aborts.
+ *   - Shapes: M, N >= 0 (M == 0 or N == 0 is a valid no-op, and a matrix with no rows may be
+ *     passed as NULL), 0 < K <= CONVROT_MAX_K,
+ *     K % 32 == 0 and K % g == 0 (the paper defines no padding for a ragged last block).
+ *     Data pointers must be 16-byte aligned, scale pointers 4-byte aligned.
+ *
+ * Packed 4-bit layout ("canonical", shared by activations and weights): a row of K codes is
+ * K/2 bytes; byte j holds code 2j in bits 0-3 and code 2j+1 in bits 4-7, each a 4-bit two's
+ * complement integer in [-7, 7] (-8 is never produced).
+ *
+ * Quantiser (both operands): a = max_k |x'[k]| over the rotated row, s = a / 7 in fp32 (s = 1
+ * when a == 0), q = clamp(round_half_even(x' / s), -7, 7).
+ */
+#ifndef CONVROT_H
+#define CONVROT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CONVROT_VERSION 100          /* major*10000 + minor*100 + patch */
+#define CONVROT_MAX_K 65536          /* longest row the single-pass rotate+quantise kernel holds on chip */
+
+typedef enum convrot_status {
+    CONVROT_OK = 0,
+    CONVROT_ERR_NULL = -1,       /* a required pointer is NULL                                     */
+    CONVROT_ERR_SHAPE = -2,      /* M or N < 0, K <= 0, K > CONVROT_MAX_K, K % 32 != 0, K % g != 0 */
+    CONVROT_ERR_GROUP = -3,      /* g not in {4, 16, 64, 256, 1024}                                */
+    CONVROT_ERR_ALIGN = -4,      /* a pointer is not aligned as required                           */
+    CONVROT_ERR_WORKSPACE = -5,  /* workspace_bytes < convrot_workspace_bytes(M, K)                */
+    CONVROT_ERR_HIP = -6         /* a launch failed; the HIP error is left for hipGetLastError()   */
+} convrot_status;
+
+/* Host.  Static string for a status code ("unknown status" for anything else). */
+const char *convrot_status_string(int status);
+
+/* Host.  CONVROT_VERSION of the loaded library. */
+int convrot_version(void);
+
+/* Host.  Bytes of a packed code matrix with `rows` rows of K codes: rows * K / 2.  0 on bad input. */
+size_t convrot_packed_bytes(int64_t rows, int64_t K);
+
+/* Host.  Bytes of workspace convlinear4bit_forward needs for an [M, K] activation: the packed
+ * codes (rounded up to 256 bytes) followed by M fp32 scales (rounded up to 256).  0 on bad input. */
+size_t convrot_workspace_bytes(int64_t M, int64_t K);
+
+/*
+ * Offline weight preparation (Eq. 12-13, Sec. 5.2 "per-channel"): W' = R_g(W); for each output
+ * channel n, s_w[n] = max_k |W'[n,k]| / 7 and q_w[n,:] = Q4(W'[n,:]); packed.
+ *   W_bf16   DEVICE in   [N, K] bf16
+ *   Wq       DEVICE out  [N, K/2] bytes, canonical packed layout
+ *   w_scale  DEVICE out  [N] fp32
+ */
+int convrot_prepare_weight(const void *W_bf16, int64_t N, int64_t K, int group,
+                           void *Wq, float *w_scale, void *stream);
+
+/*
+ * Online activation path (Sec. 4.2 + Eq. 1, Sec. 5.2 "per-token"): X' = R_g(X), per-token scale,
+ * 4-bit codes, packed - one pass over X.
+ *   X_bf16   DEVICE in   [M, K] bf16
+ *   Xq       DEVICE out  [M, K/2] bytes, canonical packed layout
+ *   x_scale  DEVICE out  [M] fp32
+ */
+int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group,
+                         void *Xq, float *x_scale, void *stream);
+
+/*
+ * W4A4 GEMM with the dequantisation fused (Sec. 4.3; suppl. Sec. B lists them as two stages):
+ * Y[m,n] = bf16( (sum_k q_x[m,k] q_w[n,k]) * x_scale[m] * w_scale[n] ).
+ *   Xq, Wq            DEVICE in   packed codes [M, K/2], [N, K/2]
+ *   x_scale, w_scale  DEVICE in   [M], [N] fp32
+ *   Y_bf16            DEVICE out  [M, N] bf16
+ */
+int convrot_w4a4_gemm_dequant(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
+                              int64_t M, int64_t N, int64_t K, void *Y_bf16, void *stream);
+
+/*
+ * The whole ConvLinear4bit forward (Sec. 4.3): convrot_rotquant_act into the workspace, then
+ * convrot_w4a4_gemm_dequant, on one stream.
+ *   X_bf16     DEVICE in   [M, K] bf16
+ *   Wq         DEVICE in   [N, K/2] from convrot_prepare_weight (same `group`)
+ *   w_scale    DEVICE in   [N]
+ *   Y_bf16     DEVICE out  [M, N] bf16
+ *   workspace  DEVICE scratch, 256-byte aligned, at least convrot_workspace_bytes(M, K) bytes;
+ *              holds the activation codes and scales after the call.
+ */
+int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_scale,
+                           int64_t M, int64_t N, int64_t K, int group, void *Y_bf16,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Gate / debug export, not a hot-path call: the raw integer accumulators of the GEMM stage
+ * (Sec. 4.3), acc[m,n] = sum_k q_x[m,k] q_w[n,k], so that the GEMM can be checked bit for bit.
+ *   acc  DEVICE out  [M, N] int32
+ */
+int convrot_w4a4_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K,
+                          int32_t *acc, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONVROT_H */

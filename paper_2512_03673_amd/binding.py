@@ -1,0 +1,168 @@
+"""ctypes binding of libconvrot: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch is used for device memory and streams, nothing
+else); every step of the path runs inside the library's kernels.  There is no fallback: if the
+shared library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconvrot.so")
+
+STATUS_NAMES = {0: "CONVROT_OK", -1: "CONVROT_ERR_NULL", -2: "CONVROT_ERR_SHAPE", -3: "CONVROT_ERR_GROUP",
+                -4: "CONVROT_ERR_ALIGN", -5: "CONVROT_ERR_WORKSPACE", -6: "CONVROT_ERR_HIP"}
+
+# every symbol include/convrot.h declares
+EXPORTS = ("convrot_status_string", "convrot_version", "convrot_packed_bytes", "convrot_workspace_bytes",
+           "convrot_prepare_weight", "convrot_rotquant_act", "convrot_w4a4_gemm_dequant",
+           "convlinear4bit_forward", "convrot_w4a4_gemm_i32")
+
+_lib = None
+
+
+class ConvRotError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {STATUS_NAMES.get(status, status)} ({status_string(status)})")
+
+
+def load() -> ctypes.CDLL:
+    """Load libconvrot.so (built by ``python -m paper_2512_03673_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is not built; run `python -m paper_2512_03673_amd.build` (hipcc, gfx950). "
+            "There is no CPU fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    lib.convrot_status_string.argtypes = [i32]
+    lib.convrot_status_string.restype = ctypes.c_char_p
+    lib.convrot_version.argtypes = []
+    lib.convrot_version.restype = i32
+    lib.convrot_packed_bytes.argtypes = [i64, i64]
+    lib.convrot_packed_bytes.restype = sz
+    lib.convrot_workspace_bytes.argtypes = [i64, i64]
+    lib.convrot_workspace_bytes.restype = sz
+    lib.convrot_prepare_weight.argtypes = [vp, i64, i64, i32, vp, vp, vp]
+    lib.convrot_rotquant_act.argtypes = [vp, i64, i64, i32, vp, vp, vp]
+    lib.convrot_w4a4_gemm_dequant.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp]
+    lib.convlinear4bit_forward.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, sz, vp]
+    lib.convrot_w4a4_gemm_i32.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    for name in EXPORTS[4:]:
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().convrot_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load().convrot_version())
+
+
+def packed_bytes(rows: int, K: int) -> int:
+    return int(load().convrot_packed_bytes(rows, K))
+
+
+def workspace_bytes(M: int, K: int) -> int:
+    return int(load().convrot_workspace_bytes(M, K))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise ConvRotError(status, what)
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> None:
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU")
+
+
+def convrot_prepare_weight(W: torch.Tensor, group: int, Wq: Optional[torch.Tensor] = None,
+                           w_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """W bf16 [N, K] -> (Wq uint8 [N, K/2], w_scale f32 [N])."""
+    _dev(W, torch.bfloat16, "W")
+    N, K = W.shape
+    Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device) if Wq is None else Wq
+    w_scale = torch.empty((N,), dtype=torch.float32, device=W.device) if w_scale is None else w_scale
+    _check(load().convrot_prepare_weight(_ptr(W), N, K, group, _ptr(Wq), _ptr(w_scale), _stream(stream)),
+           "convrot_prepare_weight")
+    return Wq, w_scale
+
+
+def convrot_rotquant_act(X: torch.Tensor, group: int, Xq: Optional[torch.Tensor] = None,
+                         x_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """X bf16 [M, K] -> (Xq uint8 [M, K/2], x_scale f32 [M])."""
+    _dev(X, torch.bfloat16, "X")
+    M, K = X.shape
+    Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=X.device) if Xq is None else Xq
+    x_scale = torch.empty((M,), dtype=torch.float32, device=X.device) if x_scale is None else x_scale
+    _check(load().convrot_rotquant_act(_ptr(X), M, K, group, _ptr(Xq), _ptr(x_scale), _stream(stream)),
+           "convrot_rotquant_act")
+    return Xq, x_scale
+
+
+def convrot_w4a4_gemm_dequant(Xq: torch.Tensor, x_scale: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor,
+                              Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Packed codes + scales -> Y bf16 [M, N]."""
+    _dev(Xq, torch.uint8, "Xq"); _dev(Wq, torch.uint8, "Wq")
+    _dev(x_scale, torch.float32, "x_scale"); _dev(w_scale, torch.float32, "w_scale")
+    M, Kb = Xq.shape
+    N, Kb2 = Wq.shape
+    if Kb != Kb2:
+        raise ValueError("K mismatch")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=Xq.device) if Y is None else Y
+    _check(load().convrot_w4a4_gemm_dequant(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), M, N, 2 * Kb,
+                                            _ptr(Y), _stream(stream)), "convrot_w4a4_gemm_dequant")
+    return Y
+
+
+def convrot_w4a4_gemm_i32(Xq: torch.Tensor, Wq: torch.Tensor, acc: Optional[torch.Tensor] = None,
+                          stream=None) -> torch.Tensor:
+    """Packed codes -> raw int32 accumulators [M, N] (gate / debug export)."""
+    _dev(Xq, torch.uint8, "Xq"); _dev(Wq, torch.uint8, "Wq")
+    M, Kb = Xq.shape
+    N, Kb2 = Wq.shape
+    if Kb != Kb2:
+        raise ValueError("K mismatch")
+    acc = torch.empty((M, N), dtype=torch.int32, device=Xq.device) if acc is None else acc
+    _check(load().convrot_w4a4_gemm_i32(_ptr(Xq), _ptr(Wq), M, N, 2 * Kb, _ptr(acc), _stream(stream)),
+           "convrot_w4a4_gemm_i32")
+    return acc
+
+
+def convlinear4bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor, group: int,
+                           Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                           stream=None) -> torch.Tensor:
+    """X bf16 [M, K], prepared weight -> Y bf16 [M, N]; `workspace` is a uint8 tensor of workspace_bytes(M, K)."""
+    _dev(X, torch.bfloat16, "X"); _dev(Wq, torch.uint8, "Wq"); _dev(w_scale, torch.float32, "w_scale")
+    M, K = X.shape
+    N = Wq.shape[0]
+    if Wq.shape[1] * 2 != K:
+        raise ValueError("K mismatch")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if Y is None else Y
+    if workspace is None:
+        workspace = torch.empty((max(workspace_bytes(M, K), 256),), dtype=torch.uint8, device=X.device)
+    _check(load().convlinear4bit_forward(_ptr(X), _ptr(Wq), _ptr(w_scale), M, N, K, group, _ptr(Y),
+                                         _ptr(workspace), workspace.numel(), _stream(stream)),
+           "convlinear4bit_forward")
+    return Y

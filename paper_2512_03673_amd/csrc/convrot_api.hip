@@ -1,0 +1,128 @@
+// C ABI of libconvrot (see include/convrot.h): argument validation on the host, then launches.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "convrot.h"
+#include "convrot_internal.h"
+
+namespace {
+
+inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int check_group(int g) { return (g == 4 || g == 16 || g == 64 || g == 256 || g == 1024) ? CONVROT_OK : CONVROT_ERR_GROUP; }
+
+int check_k(int64_t K) { return (K > 0 && K <= CONVROT_MAX_K && K % 32 == 0) ? CONVROT_OK : CONVROT_ERR_SHAPE; }
+
+// A matrix with zero rows may come with a null pointer (an empty allocation has no address).
+inline bool missing(const void *p, int64_t rows) { return rows > 0 && !p; }
+
+int check_rotquant(const void *in, int64_t rows, int64_t K, int group, const void *out, const float *scale)
+{
+    if (int rc = check_group(group)) return rc;
+    if (rows < 0 || rows > INT32_MAX) return CONVROT_ERR_SHAPE;
+    if (int rc = check_k(K)) return rc;
+    if (K % group != 0) return CONVROT_ERR_SHAPE;
+    if (missing(in, rows) || missing(out, rows) || missing(scale, rows)) return CONVROT_ERR_NULL;
+    if (!aligned(in, 16) || !aligned(out, 16) || !aligned(scale, 4)) return CONVROT_ERR_ALIGN;
+    return CONVROT_OK;
+}
+
+int check_gemm(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K, const void *out, uintptr_t out_align)
+{
+    if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
+    if (int rc = check_k(K)) return rc;
+    if (missing(Xq, M) || missing(Wq, N) || missing(out, M * N)) return CONVROT_ERR_NULL;
+    if (!aligned(Xq, 16) || !aligned(Wq, 16) || !aligned(out, out_align)) return CONVROT_ERR_ALIGN;
+    return CONVROT_OK;
+}
+
+inline int from_hip(hipError_t e) { return e == hipSuccess ? CONVROT_OK : CONVROT_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *convrot_status_string(int status)
+{
+    switch (status) {
+        case CONVROT_OK: return "ok";
+        case CONVROT_ERR_NULL: return "null pointer";
+        case CONVROT_ERR_SHAPE: return "bad shape (need M,N >= 0, 0 < K <= 65536, K % 32 == 0, K % group == 0)";
+        case CONVROT_ERR_GROUP: return "bad group size (need 4, 16, 64, 256 or 1024)";
+        case CONVROT_ERR_ALIGN: return "misaligned pointer";
+        case CONVROT_ERR_WORKSPACE: return "workspace too small";
+        case CONVROT_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int convrot_version(void) { return CONVROT_VERSION; }
+
+size_t convrot_packed_bytes(int64_t rows, int64_t K)
+{
+    if (rows < 0 || K <= 0 || (K & 1)) return 0;
+    return (size_t)rows * (size_t)(K / 2);
+}
+
+size_t convrot_workspace_bytes(int64_t M, int64_t K)
+{
+    if (M < 0 || K <= 0 || (K & 1)) return 0;
+    return round_up((size_t)M * (size_t)(K / 2), 256) + round_up((size_t)M * sizeof(float), 256);
+}
+
+int convrot_prepare_weight(const void *W_bf16, int64_t N, int64_t K, int group, void *Wq, float *w_scale,
+                           void *stream)
+{
+    if (int rc = check_rotquant(W_bf16, N, K, group, Wq, w_scale)) return rc;
+    return from_hip(convrot::launch_rotquant(W_bf16, N, K, group, Wq, w_scale, (hipStream_t)stream));
+}
+
+int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group, void *Xq, float *x_scale,
+                         void *stream)
+{
+    if (int rc = check_rotquant(X_bf16, M, K, group, Xq, x_scale)) return rc;
+    return from_hip(convrot::launch_rotquant(X_bf16, M, K, group, Xq, x_scale, (hipStream_t)stream));
+}
+
+int convrot_w4a4_gemm_dequant(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
+                              int64_t M, int64_t N, int64_t K, void *Y_bf16, void *stream)
+{
+    if (int rc = check_gemm(Xq, Wq, M, N, K, Y_bf16, 16)) return rc;
+    if (missing(x_scale, M) || missing(w_scale, N)) return CONVROT_ERR_NULL;
+    if (!aligned(x_scale, 4) || !aligned(w_scale, 4)) return CONVROT_ERR_ALIGN;
+    return from_hip(convrot::launch_gemm_w4a4(Xq, x_scale, Wq, w_scale, M, N, K, Y_bf16, nullptr, (hipStream_t)stream));
+}
+
+int convrot_w4a4_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K, int32_t *acc,
+                          void *stream)
+{
+    if (int rc = check_gemm(Xq, Wq, M, N, K, acc, 16)) return rc;
+    return from_hip(convrot::launch_gemm_w4a4(Xq, nullptr, Wq, nullptr, M, N, K, nullptr, acc, (hipStream_t)stream));
+}
+
+int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_scale, int64_t M, int64_t N,
+                           int64_t K, int group, void *Y_bf16, void *workspace, size_t workspace_bytes,
+                           void *stream)
+{
+    if (int rc = check_group(group)) return rc;
+    if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
+    if (int rc = check_k(K)) return rc;
+    if (K % group != 0) return CONVROT_ERR_SHAPE;
+    if (missing(X_bf16, M) || missing(Wq, N) || missing(w_scale, N) || missing(Y_bf16, M * N) ||
+        missing(workspace, M))
+        return CONVROT_ERR_NULL;
+    if (!aligned(X_bf16, 16) || !aligned(Wq, 16) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
+        !aligned(workspace, 256))
+        return CONVROT_ERR_ALIGN;
+    if (workspace_bytes < convrot_workspace_bytes(M, K)) return CONVROT_ERR_WORKSPACE;
+
+    uint8_t *xq = static_cast<uint8_t *>(workspace);
+    float *xs = reinterpret_cast<float *>(xq + round_up((size_t)M * (size_t)(K / 2), 256));
+    hipStream_t s = (hipStream_t)stream;
+    if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
+    return from_hip(convrot::launch_gemm_w4a4(xq, xs, Wq, w_scale, M, N, K, Y_bf16, nullptr, s));
+}
+
+}  // extern "C"

@@ -1,0 +1,20 @@
+// Internal launch interface between the C ABI (convrot_api.hip) and the kernels.
+// Shapes are validated by the caller; these only pick a configuration and launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace convrot {
+
+// Rotate + quantise + pack `rows` rows of K bf16 values (group in {4,16,64,256,1024}).
+hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, void *Xq, float *scale,
+                           hipStream_t stream);
+
+// W4A4 GEMM on packed codes.  Exactly one of Y_bf16 / acc_i32 is non-null:
+//   Y_bf16 : dequantised bf16 output (needs x_scale, w_scale)
+//   acc_i32: raw int32 accumulators
+hipError_t launch_gemm_w4a4(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
+                            int64_t M, int64_t N, int64_t K, void *Y_bf16, int32_t *acc_i32,
+                            hipStream_t stream);
+
+}  // namespace convrot

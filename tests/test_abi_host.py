@@ -1,0 +1,96 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and argument
+validation returns the documented status before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "convrot.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2512_03673_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2512_03673_amd import build
+        build.build(verbose=False)
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(conv(?:rot|linear4bit)_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    from paper_2512_03673_amd import binding
+    names = declared_symbols()
+    assert len(names) == 9
+    assert sorted(binding.EXPORTS) == names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_size_queries_and_strings(lib):
+    from paper_2512_03673_amd import binding as b
+    assert b.version() == 100
+    assert b.packed_bytes(4608, 3072) == 4608 * 1536
+    assert b.packed_bytes(-1, 32) == 0 and b.packed_bytes(4, 33) == 0
+    # codes rounded up to 256 B + scales rounded up to 256 B
+    assert b.workspace_bytes(4608, 3072) == 4608 * 1536 + 4608 * 4
+    assert b.workspace_bytes(3, 32) == 256 + 256
+    assert b.workspace_bytes(0, 32) == 0
+    assert b.status_string(0) == "ok"
+    assert "group" in b.status_string(-3)
+    assert b.status_string(-99) == "unknown status"
+
+
+def test_argument_validation_without_a_device(lib):
+    # fake, suitably aligned addresses: validation must reject before touching them
+    A = 0x10000
+    f = lib.convrot_rotquant_act
+    assert f(None, 4, 1024, 16, A, A, None) == -1
+    assert f(A, 4, 1024, 16, None, A, None) == -1
+    assert f(A, 4, 1024, 16, A, None, None) == -1
+    assert f(A, 4, 1024, 8, A, A, None) == -3
+    assert f(A, -1, 1024, 16, A, A, None) == -2
+    assert f(A, 4, 0, 16, A, A, None) == -2
+    assert f(A, 4, 1040, 16, A, A, None) == -2          # K % 32 != 0
+    assert f(A, 4, 96, 64, A, A, None) == -2            # K % g != 0
+    assert f(A, 4, 131072, 16, A, A, None) == -2        # K > CONVROT_MAX_K
+    assert f(A + 8, 4, 1024, 16, A, A, None) == -4
+    assert f(A, 4, 1024, 16, A + 4, A, None) == -4
+    assert f(A, 4, 1024, 16, A, A + 2, None) == -4
+    p = lib.convrot_prepare_weight
+    assert p(None, 4, 1024, 16, A, A, None) == -1
+    assert p(A, 4, 1024, 3, A, A, None) == -3
+    g = lib.convrot_w4a4_gemm_dequant
+    assert g(None, A, A, A, 4, 4, 1024, A, None) == -1
+    assert g(A, None, A, A, 4, 4, 1024, A, None) == -1
+    assert g(A, A, A, A, 4, -4, 1024, A, None) == -2
+    assert g(A, A, A, A, 4, 4, 1000, A, None) == -2
+    assert g(A, A, A + 1, A, 4, 4, 1024, A, None) == -4
+    r = lib.convrot_w4a4_gemm_i32
+    assert r(A, A, 4, 4, 1024, None, None) == -1
+    assert r(A, A, 4, 4, 48, A, None) == -2
+    fw = lib.convlinear4bit_forward
+    assert fw(A, A, A, 4, 4, 1024, 16, A, None, 1 << 20, None) == -1
+    assert fw(A, A, A, 4, 4, 1024, 5, A, A, 1 << 20, None) == -3
+    assert fw(A, A, A, 4, 4, 1024, 16, A, A + 16, 1 << 20, None) == -4
+    assert fw(A, A, A, 4, 4, 1024, 16, A, A, 100, None) == -5
+    # empty problems are valid no-ops and launch nothing
+    assert f(A, 0, 1024, 16, A, A, None) == 0
+    assert g(A, A, A, A, 0, 4, 1024, A, None) == 0
+    assert g(A, A, A, A, 4, 0, 1024, A, None) == 0
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2512_03673_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "oracle/" not in text, fn

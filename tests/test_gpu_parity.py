@@ -1,0 +1,200 @@
+"""GPU parity: libconvrot (HIP, through the C ABI) against the CPU oracle, element by element.
+
+Gates: 4-bit codes identical on >= 99.99 % of elements and never more than 1 LSB apart;
+int32 GEMM bit-exact on identical codes; bf16 output max relative error <= 1e-2 (relative to
+max |Y|) with cosine similarity >= 0.9999, and within one bf16 step when the codes are identical.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import (bf16_to_host_bits, bf16_ulp_diff, bits_to_f64, check_codes, check_output, to_dev_bf16,
+                      unpack_host)
+from paper_2512_03673_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+GROUPS = (4, 16, 64, 256, 1024)
+
+
+@pytest.fixture(scope="module")
+def cr():
+    from paper_2512_03673_amd import binding
+    binding.load()
+    return binding
+
+
+def gpu_rotquant(cr, bits, g, weight=False):
+    x = to_dev_bf16(bits)
+    fn = cr.convrot_prepare_weight if weight else cr.convrot_rotquant_act
+    q, s = fn(x, g)
+    torch.cuda.synchronize()
+    return q.cpu().numpy(), s.cpu().numpy()
+
+
+# ------------------------------------------------------------------ kernel A: rotate + quantise + pack
+@pytest.mark.parametrize("g", GROUPS)
+@pytest.mark.parametrize("M,K", [(37, 1024), (5, 3072), (130, 4096), (3, 12288), (9, 15360), (2, 65536), (67, 2048)])
+def test_rotquant_matches_oracle(cr, g, M, K):
+    if K % g:
+        pytest.skip("K not a multiple of g")
+    spec = wl.LayerSpec(f"rq_{M}_{K}", M=M, K=K, N=8, group=g, x_col_count=max(1, K // 100),
+                        x_row_count=1, seed=11)
+    x = wl.make_activation(spec)
+    q, s = gpu_rotquant(cr, x, g)
+    qo, so = oracle.rotquant(x, g)
+    check_codes(unpack_host(q), s, qo, so, f"g={g} M={M} K={K}")
+
+
+@pytest.mark.parametrize("g", (4, 16, 64, 256))
+def test_rotquant_small_k_multiples_of_32(cr, g):
+    for K in (32, 96, 256, 288, 1056):
+        if K % g:
+            continue
+        rng = np.random.default_rng(K + g)
+        x = wl.f32_to_bf16_bits(rng.standard_normal((19, K)).astype(np.float32))
+        q, s = gpu_rotquant(cr, x, g)
+        qo, so = oracle.rotquant(x, g)
+        check_codes(unpack_host(q), s, qo, so, f"g={g} K={K}")
+
+
+@pytest.mark.parametrize("g", GROUPS)
+def test_rotquant_closed_forms_on_gpu(cr, g):
+    # the same special cases that pin the oracle, now on the HIP path: exact equality expected
+    K = 4 * g if g >= 16 else 64
+    x = np.zeros((4, K), dtype=np.float32)
+    x[0, 2 * g + (g - 2)] = 1.0          # one-hot -> 7 * H[j], scale 1/(7 sqrt g)
+    x[1, :] = -0.75                      # constant -> all -7, scale 0.75/7
+    x[3, 5] = -3.0                       # row 2 stays zero -> scale 1, codes 0
+    bits = wl.f32_to_bf16_bits(x)
+    q, s = gpu_rotquant(cr, bits, g)
+    qo, so = oracle.rotquant(bits, g)
+    assert np.array_equal(unpack_host(q), qo)
+    assert np.array_equal(s, so)
+    assert s[2] == np.float32(1.0) and not q[2].any()
+
+
+def test_prepare_weight_is_the_same_operation(cr):
+    spec = wl.CONFIGS["cfg1_tiny"][0]
+    w = wl.make_weight(spec)
+    q, s = gpu_rotquant(cr, w, 16, weight=True)
+    qo, so = oracle.rotquant(w, 16)
+    check_codes(unpack_host(q), s, qo, so, "prepare_weight")
+
+
+# ------------------------------------------------------------------ kernel B: integer GEMM
+@pytest.mark.parametrize("M,N,K", [(256, 256, 128), (300, 520, 1024), (1, 1, 32), (33, 7, 96), (257, 513, 3072),
+                                   (64, 1030, 12288), (513, 258, 160)])
+def test_gemm_i32_bit_exact(cr, M, N, K):
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    # extreme rows: every product +-49, reaches the accumulator bound
+    qx[0, :] = 7
+    qw[0, :] = -7
+    acc = cr.convrot_w4a4_gemm_i32(torch.from_numpy(oracle.pack4(qx)).cuda(), torch.from_numpy(oracle.pack4(qw)).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 520, 1024), (129, 1026, 3072), (31, 5, 64)])
+def test_gemm_dequant_on_identical_codes(cr, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    sx = np.exp(rng.uniform(-6, 2, M)).astype(np.float32)
+    sw = np.exp(rng.uniform(-9, -4, N)).astype(np.float32)
+    y = cr.convrot_w4a4_gemm_dequant(torch.from_numpy(oracle.pack4(qx)).cuda(), torch.from_numpy(sx).cuda(),
+                                     torch.from_numpy(oracle.pack4(qw)).cuda(), torch.from_numpy(sw).cuda())
+    torch.cuda.synchronize()
+    yb = bf16_to_host_bits(y)
+    yo = oracle.dequant(oracle.int_gemm(qx, qw), sx, sw)
+    # fp32 (acc*sx)*sw then one rounding vs the double product: at most one bf16 step, almost always none
+    d = bf16_ulp_diff(yb, yo)
+    assert d.max() <= 1
+    assert (d == 0).mean() > 0.999
+    check_output(yb, yo, "dequant")
+
+
+# ------------------------------------------------------------------ whole forward
+@pytest.mark.parametrize("g", (4, 16, 64, 256))
+def test_forward_tiny_config(cr, g):
+    base = wl.CONFIGS["cfg1_tiny"][0]
+    spec = wl.LayerSpec(**{**base.__dict__, "group": g})
+    x, w = wl.make_layer(spec)
+    wq, ws = cr.convrot_prepare_weight(to_dev_bf16(w), g)
+    y = cr.convlinear4bit_forward(to_dev_bf16(x), wq, ws, g)
+    torch.cuda.synchronize()
+    yo = oracle.convlinear4bit(x, w, g)
+    check_output(bf16_to_host_bits(y), yo, f"forward g={g}")
+
+
+def test_forward_equals_two_stage_calls(cr):
+    spec = wl.LayerSpec("fwd2", M=300, K=1024, N=520, group=16, seed=2)
+    x, w = wl.make_layer(spec)
+    xd = to_dev_bf16(x)
+    wq, ws = cr.convrot_prepare_weight(to_dev_bf16(w), 16)
+    y1 = cr.convlinear4bit_forward(xd, wq, ws, 16)
+    xq, xs = cr.convrot_rotquant_act(xd, 16)
+    y2 = cr.convrot_w4a4_gemm_dequant(xq, xs, wq, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+    check_output(bf16_to_host_bits(y1), oracle.convlinear4bit(x, w, 16), "forward ragged")
+
+
+def test_forward_exact_on_representable_inputs(cr):
+    g, K, M, N = 16, 64, 3, 5
+    x = np.zeros((M, K), dtype=np.float32)
+    x[0], x[1], x[2] = 1.0, -2.0, 0.5
+    w = np.zeros((N, K), dtype=np.float32)
+    for n in range(N):
+        w[n, (n * 7) % K] = 0.25 * (n + 1)
+    wq, ws = cr.convrot_prepare_weight(to_dev_bf16(wl.f32_to_bf16_bits(w)), g)
+    y = cr.convlinear4bit_forward(to_dev_bf16(wl.f32_to_bf16_bits(x)), wq, ws, g)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_to_f64(bf16_to_host_bits(y)), x.astype(np.float64) @ w.astype(np.float64).T)
+
+
+# ------------------------------------------------------------------ edge cases and error paths
+def test_empty_inputs_are_noops(cr):
+    dev = torch.device("cuda")
+    xq, xs = cr.convrot_rotquant_act(torch.empty((0, 1024), dtype=torch.bfloat16, device=dev), 16)
+    assert xq.shape == (0, 512) and xs.shape == (0,)
+    wq = torch.zeros((8, 512), dtype=torch.uint8, device=dev)
+    ws = torch.ones((8,), dtype=torch.float32, device=dev)
+    y = cr.convrot_w4a4_gemm_dequant(xq, xs, wq, ws)
+    assert y.shape == (0, 8)
+    y = cr.convlinear4bit_forward(torch.empty((0, 1024), dtype=torch.bfloat16, device=dev), wq, ws, 16)
+    assert y.shape == (0, 8)
+    torch.cuda.synchronize()
+
+
+def test_error_statuses_write_nothing(cr):
+    dev = torch.device("cuda")
+    x = torch.zeros((4, 1024), dtype=torch.bfloat16, device=dev)
+    q = torch.full((4, 512), 0xAB, dtype=torch.uint8, device=dev)
+    s = torch.full((4,), 5.0, dtype=torch.float32, device=dev)
+    for g, want in ((8, -3), (0, -3), (2048, -3)):
+        with pytest.raises(cr.ConvRotError) as e:
+            cr.convrot_rotquant_act(x, g, q, s)
+        assert e.value.status == want
+    x48 = torch.zeros((4, 48), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(cr.ConvRotError) as e:
+        cr.convrot_rotquant_act(x48, 16)           # K % 32 != 0
+    assert e.value.status == -2
+    x96 = torch.zeros((4, 96), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(cr.ConvRotError) as e:
+        cr.convrot_rotquant_act(x96, 64)           # K % g != 0
+    assert e.value.status == -2
+    lib = cr.load()
+    assert lib.convrot_rotquant_act(None, 4, 1024, 16, q.data_ptr(), s.data_ptr(), None) == -1
+    assert lib.convrot_rotquant_act(x.data_ptr() + 2, 4, 1024, 16, q.data_ptr(), s.data_ptr(), None) == -4
+    ws = torch.empty((256,), dtype=torch.uint8, device=dev)
+    y = torch.empty((4, 8), dtype=torch.bfloat16, device=dev)
+    wq = torch.zeros((8, 512), dtype=torch.uint8, device=dev)
+    wsc = torch.ones((8,), dtype=torch.float32, device=dev)
+    assert lib.convlinear4bit_forward(x.data_ptr(), wq.data_ptr(), wsc.data_ptr(), 4, 8, 1024, 16, y.data_ptr(),
+                                      ws.data_ptr(), 256, None) == -5
+    torch.cuda.synchronize()
+    assert (q == 0xAB).all() and (s == 5.0).all()
