@@ -20,9 +20,9 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
+def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
     """Compile every HIP source (always recompiles) and link the shared library."""
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build", os.path.basename(out).replace(".so", ""))
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src: str) -> str:
@@ -35,14 +35,19 @@ def build(verbose: bool = True, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    tmp = LIB + f".tmp{os.getpid()}"
+    tmp = out + f".tmp{os.getpid()}"
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":
-    print(build(extra_flags=sys.argv[1:]))
+    # usage: python -m paper_2512_03673_amd.build [--out path.so] [extra hipcc flags ...]
+    argv = sys.argv[1:]
+    target = LIB
+    if argv[:1] == ["--out"]:
+        target, argv = os.path.abspath(argv[1]), argv[2:]
+    print(build(extra_flags=argv, out=target))

@@ -14,10 +14,22 @@
 // (|256 acc| <= 256 * 49 * K < 2^31 for K <= 65536) and the factor 2^-8 is folded, exactly,
 // into the epilogue.
 //
+// Data movement.  A block owns a 256 x 256 output tile (4 wavefronts, 128 x 128 each, 256
+// accumulator registers per lane).  Packed codes travel HBM -> LDS with global_load_lds_dwordx4
+// (no register staging) into a ring of 4 stages of 128 codes (64 bytes) of K; the codes stay
+// packed in LDS and are widened in registers after ds_read_b128, 3 VALU operations per MFMA.
+// LDS rows are 64 bytes; the four 16-byte pieces of a row are XOR-swizzled by row so that the
+// fragment reads (32 consecutive rows, one piece) touch every bank once.  The swizzle is applied
+// on the global side: an LDS-direct load writes lane l at base + 16 l, so lane l simply fetches
+// the piece that belongs there.
+//
 // The MFMA's row operand is the W tile and its column operand the X tile, so that a lane ends up
-// with four consecutive n for one m and the bf16 output is written in 8-byte pieces.
+// with four consecutive n for one m; the epilogue scales, rounds to bf16, transposes through LDS
+// and writes 16 bytes per lane, 256 contiguous bytes per output row.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "convrot_internal.h"
 
@@ -27,19 +39,73 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 
-constexpr int kStageBytes = 64;   // packed bytes of K per row per LDS stage (128 codes)
-constexpr int kLdsStride = 80;    // row pitch in LDS: 64 + 16 bytes of padding (bank spread for b128 reads)
+constexpr int BM = 256, BN = 256;        // block tile
+constexpr int kThreads = 256;            // 4 wavefronts, 2 x 2
+constexpr int WTM = 128, WTN = 128;      // wavefront tile
+constexpr int FM = WTM / 32, FN = WTN / 32;
+#ifndef CONVROT_GEMM_ROW_BYTES
+#define CONVROT_GEMM_ROW_BYTES 64
+#endif
+#ifndef CONVROT_GEMM_STAGES
+#define CONVROT_GEMM_STAGES 4
+#endif
+constexpr int kRowBytes = CONVROT_GEMM_ROW_BYTES;         // packed bytes of K per row per stage (64 B = 128 codes)
+constexpr int kStages = CONVROT_GEMM_STAGES;
+constexpr int kPieces = kRowBytes / 16;                   // 16-byte pieces per LDS row
+constexpr int kSubSteps = kRowBytes / 32;                 // K64 steps (one ds_read_b128 per fragment) per stage
+constexpr int kStageBytes = (BM + BN) * kRowBytes;
+constexpr int kLdsBytes = kStages * kStageBytes;          // 128 KB
+constexpr int kChunksPerWave = kStageBytes / 1024 / 4;    // 1 KB LDS-direct loads per wavefront per stage
+constexpr int kRowsPerChunk = 1024 / kRowBytes;
+constexpr int kEpiPitch = WTN * 2 + 16;                   // bf16 row of the wavefront tile + pad
 constexpr int kNumXcd = 8;
+
+static_assert(kRowBytes == 64 || kRowBytes == 128, "row bytes");
+static_assert(kChunksPerWave * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
+static_assert(4 * 32 * kEpiPitch <= kLdsBytes, "epilogue staging must fit the ring");
+static_assert(kLdsBytes <= 160 * 1024, "LDS");
+
+// 16 zero bytes for LDS-direct loads that fall past the end of K.
+__device__ const uint4 kZeroPiece = {0u, 0u, 0u, 0u};
 
 __device__ __forceinline__ uint32_t nib_lo(uint32_t p) { return (p << 4) & 0xF0F0F0F0u; }
 __device__ __forceinline__ uint32_t nib_hi(uint32_t p) { return p & 0xF0F0F0F0u; }
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+// Which of the four 16-byte slots of its LDS row a piece lands in: slot = piece ^ swz(row).
+// For any 8 consecutive rows the (row & 1, slot) pairs are distinct (32 banks), and for any 16
+// consecutive rows the (row & 3, slot) pairs are distinct (64 banks).
+__device__ __forceinline__ int swz(int row)
 {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    if constexpr (kPieces == 4) return ((row >> 1) ^ (row >> 3)) & 3;
+    else return (row ^ (row >> 3)) & 7;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    // gfx9 encoding: vmcnt = {imm[15:14], imm[3:0]}, expcnt = imm[6:4], lgkmcnt = imm[11:8]
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+// global_load_lds_dwordx4: lane l copies 16 bytes from its global address to LDS address M0 + 16 l.
+__device__ __forceinline__ void lds_dma16(const uint8_t *base, uint32_t lane_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void lds_dma16_addr(const uint8_t *lane_ptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(lane_ptr), "s"(lds_addr) : "memory");
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    v2bf r = __builtin_convertvector((v2f){a, b}, v2bf);   // v_cvt_pk_bf16_f32: round to nearest even
+    return *reinterpret_cast<uint32_t *>(&r);
 }
 
 // Tile order: blocks are dealt round-robin to the 8 XCDs by the hardware, each XCD has its own
@@ -63,64 +129,82 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
 
 }  // namespace
 
-template <int BM, int BN, int WGM, int WGN, bool RAW>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_w4a4_kernel(
+template <bool RAW>
+__global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ x_scale, const uint8_t *__restrict__ Wq,
     const float *__restrict__ w_scale, int M, int N, int K, uint16_t *__restrict__ Y,
     int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
 {
-    constexpr int NT = WGM * WGN * 64;
-    constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wavefront tile
-    constexpr int FM = WTM / 32, FN = WTN / 32;    // 32x32 MFMA tiles per wavefront
-    constexpr int XP = BM * 4 / NT, WP = BN * 4 / NT;  // 16-byte pieces per thread per stage
-    static_assert(BM * 4 % NT == 0 && BN * 4 % NT == 0, "tile/threads mismatch");
-
-    constexpr int kBufBytes = (BM + BN) * kLdsStride;
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    uint8_t(*lds)[kBufBytes] = reinterpret_cast<uint8_t(*)[kBufBytes]>(lds_raw);
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
     int tm, tn;
     if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave % WGM) * WTM, wn0 = (wave / WGM) * WTN;
-    const int Kb = K >> 1;  // packed bytes per row
-    const int KT = (Kb + kStageBytes - 1) / kStageBytes;  // the last stage may be partial: zero-filled
+    const int wm0 = (wave & 1) * WTM, wn0 = (wave >> 1) * WTN;
+    const int Kb = K >> 1;                                   // packed bytes per row
+    const int KT = (Kb + kRowBytes - 1) / kRowBytes;         // stages; the last may be partial (zero-filled)
 
-    // global -> register staging addresses (rows past the edge re-read the last valid row)
-    const uint8_t *xg[XP];
-    const uint8_t *wg[WP];
-    int xl[XP], wl[WP];
+    // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
+    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..511 are W); lane l fills slot l & 3 of row l >> 2.
+    const uint8_t *xtile = Xq + (int64_t)m0 * Kb;
+    const uint8_t *wtile = Wq + (int64_t)n0 * Kb;
+    uint32_t goff[kChunksPerWave];   // byte offset of this lane's piece inside the operand tile, stage 0
+    int gcol[kChunksPerWave];        // byte column of that piece inside the 64-byte stage row
 #pragma unroll
-    for (int i = 0; i < XP; ++i) {
-        const int p = tid + NT * i, r = p >> 2, c = p & 3;
-        xg[i] = Xq + (int64_t)min(m0 + r, M - 1) * Kb + c * 16;
-        xl[i] = r * kLdsStride + c * 16;
-    }
-#pragma unroll
-    for (int i = 0; i < WP; ++i) {
-        const int p = tid + NT * i, r = p >> 2, c = p & 3;
-        wg[i] = Wq + (int64_t)min(n0 + r, N - 1) * Kb + c * 16;
-        wl[i] = (BM + r) * kLdsStride + c * 16;
+    for (int i = 0; i < kChunksPerWave; ++i) {
+        const int c = wave + 4 * i;
+        const int row_t = kRowsPerChunk * c + lane / kPieces;
+        const int piece = (lane % kPieces) ^ swz(row_t);
+        const bool is_x = i < kChunksPerWave / 2;            // c < 16
+        const int r = is_x ? min(row_t, M - 1 - m0) : min(row_t - BM, N - 1 - n0);   // edge rows re-read the last valid row
+        goff[i] = (uint32_t)r * (uint32_t)Kb + piece * 16;
+        gcol[i] = piece * 16;
     }
 
-    uint4 xr[XP], wr[WP];
-    const int piece_col = (tid & 3) * 16;  // NT is a multiple of 4: every piece of a thread has the same column
+    // LDS-direct loads are issued from inline assembly so that the compiler does not serialise every
+    // later LDS read behind them; completion is tracked by hand with vmcnt (they retire in order).
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
+    const uint32_t wave_lds = lds_base + __builtin_amdgcn_readfirstlane(wave) * 1024;
+    const int KT_full = Kb / kRowBytes;
     auto load_stage = [&](int kt) {
-        const int koff = kt * kStageBytes;
-        const bool in_row = koff + piece_col < Kb;  // zero codes past the end of K add nothing
+        const uint32_t sl = wave_lds + (kt % kStages) * kStageBytes;   // chunk wave + 4 i sits 4096 i further on
+        const uint32_t koff = (uint32_t)kt * kRowBytes;
+        if (kt < KT_full) {
+            const uint8_t *xb = xtile + koff, *wb = wtile + koff;
 #pragma unroll
-        for (int i = 0; i < XP; ++i)
-            xr[i] = in_row ? *reinterpret_cast<const uint4 *>(xg[i] + koff) : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < kChunksPerWave; ++i)
+                lds_dma16(i < kChunksPerWave / 2 ? xb : wb, goff[i], sl + i * 4096);
+        } else if (kt < KT) {   // ragged last stage: pieces past the end of K come from a zero constant
 #pragma unroll
-        for (int i = 0; i < WP; ++i)
-            wr[i] = in_row ? *reinterpret_cast<const uint4 *>(wg[i] + koff) : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < kChunksPerWave; ++i) {
+                const uint8_t *g = (i < kChunksPerWave / 2 ? xtile : wtile) + (goff[i] + koff);
+                if ((int)koff + gcol[i] >= Kb) g = reinterpret_cast<const uint8_t *>(&kZeroPiece);
+                lds_dma16_addr(g, sl + i * 4096);
+            }
+        } else {                // past the end: a dummy fill keeps the vmcnt bookkeeping uniform
+#pragma unroll
+            for (int i = 0; i < kChunksPerWave; ++i)
+                lds_dma16_addr(reinterpret_cast<const uint8_t *>(&kZeroPiece), sl + i * 4096);
+        }
     };
-    auto store_stage = [&](int buf) {
+
+    // ---- LDS -> registers: fragment of 32 rows x 32 packed codes per lane-half
+    const int frow = lane & 31;
+    const int fswz = swz(frow);                              // tile rows differ from frow by multiples of 32
+    int foff[kSubSteps];                                     // per K64 step: byte offset inside a 32-row slab
 #pragma unroll
-        for (int i = 0; i < XP; ++i) *reinterpret_cast<uint4 *>(&lds[buf][xl[i]]) = xr[i];
+    for (int ks = 0; ks < kSubSteps; ++ks) foff[ks] = frow * kRowBytes + (((2 * ks + (lane >> 5)) ^ fswz) << 4);
+    const int xslab = wm0 * kRowBytes;
+    const int wslab = (BM + wn0) * kRowBytes;
+
+    uint4 px[FM], pw[FN];
+    auto read_frags = [&](int kt, int ks) {
+        const uint8_t *sbase = lds + (kt % kStages) * kStageBytes + foff[ks];
 #pragma unroll
-        for (int i = 0; i < WP; ++i) *reinterpret_cast<uint4 *>(&lds[buf][wl[i]]) = wr[i];
+        for (int i = 0; i < FM; ++i) px[i] = *reinterpret_cast<const uint4 *>(sbase + xslab + i * 32 * kRowBytes);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) pw[j] = *reinterpret_cast<const uint4 *>(sbase + wslab + j * 32 * kRowBytes);
     };
 
     v16i acc[FM][FN];
@@ -131,62 +215,142 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_w4a4_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    const int frag_row = lane & 31;
-    const int frag_kb = (lane >> 5) * 16;
-
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_stage(kt + 1);
-
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v4i xop[FM][2], wop[FN][2];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const uint4 p = *reinterpret_cast<const uint4 *>(
-                    &lds[buf][(wm0 + i * 32 + frag_row) * kLdsStride + ks * 32 + frag_kb]);
-                xop[i][0] = v4i{(int)nib_lo(p.x), (int)nib_hi(p.x), (int)nib_lo(p.y), (int)nib_hi(p.y)};
-                xop[i][1] = v4i{(int)nib_lo(p.z), (int)nib_hi(p.z), (int)nib_lo(p.w), (int)nib_hi(p.w)};
-            }
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const uint4 p = *reinterpret_cast<const uint4 *>(
-                    &lds[buf][(BM + wn0 + j * 32 + frag_row) * kLdsStride + ks * 32 + frag_kb]);
-                wop[j][0] = v4i{(int)nib_lo(p.x), (int)nib_hi(p.x), (int)nib_lo(p.y), (int)nib_hi(p.y)};
-                wop[j][1] = v4i{(int)nib_lo(p.z), (int)nib_hi(p.z), (int)nib_lo(p.w), (int)nib_hi(p.w)};
-            }
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop[j][h], xop[i][h], acc[i][j], 0, 0, 0);
+    // Widened operands are double-buffered: while the 32 MFMAs of one K64 step run, the VALU widens
+    // the fragments of the next step in their shadow (3 VALU operations per packed dword, 96 per step).
+    v4i xop[2][FM][2], wop[2][FN][2];
+    // widen packed dword number d (0..31) of the pending fragments into buffer PAR:
+    // fragment d / 4 (0-3: X rows, 4-7: W rows), dword d % 4 -> operand half (d % 4) / 2, bytes 8 (d % 2)..
+    auto widen_dword = [&](auto PAR, auto D) {
+        constexpr int par = decltype(PAR)::value, d = decltype(D)::value;
+        constexpr int f = d / 4, c = d % 4, h = c / 2, e = (c % 2) * 2;
+        if constexpr (f < FM) {
+            const uint32_t p = c == 0 ? px[f].x : c == 1 ? px[f].y : c == 2 ? px[f].z : px[f].w;
+            xop[par][f][h][e] = (int)nib_lo(p);
+            xop[par][f][h][e + 1] = (int)nib_hi(p);
+        } else {
+            const uint32_t p = c == 0 ? pw[f - FM].x : c == 1 ? pw[f - FM].y : c == 2 ? pw[f - FM].z : pw[f - FM].w;
+            wop[par][f - FM][h][e] = (int)nib_lo(p);
+            wop[par][f - FM][h][e + 1] = (int)nib_hi(p);
         }
-
-        if (kt + 1 < KT) store_stage(buf ^ 1);
-        __syncthreads();
-    }
-
-    // Epilogue.  Lane l, register r of a 32x32 tile: m = l % 32, n = 8 (r/4) + 4 (l/32) + r % 4.
-    const bool vec_ok = RAW ? ((N & 3) == 0) : ((N & 3) == 0);
+    };
+    auto widen_range = [&](auto PAR, auto LO, auto HI) {   // dwords LO .. HI-1
+        constexpr int lo = decltype(LO)::value, hi = decltype(HI)::value;
+        if constexpr (lo < hi) {
+            widen_dword(PAR, std::integral_constant<int, lo>{});
+            if constexpr (lo + 1 < hi) widen_dword(PAR, std::integral_constant<int, lo + 1>{});
+            static_assert(hi - lo <= 2, "at most two dwords per MFMA slot");
+        }
+    };
+    auto widen_all = [&](auto PAR) {
+        constexpr int par = decltype(PAR)::value;
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int m = m0 + wm0 + i * 32 + (lane & 31);
-        if (m >= M) continue;
-        float sxm = 0.0f;
-        if constexpr (!RAW) sxm = x_scale[m] * 0.00390625f;  // 2^-8 undoes the 16*16 of the widening
+        for (int i = 0; i < FM; ++i) {
+            xop[par][i][0] = v4i{(int)nib_lo(px[i].x), (int)nib_hi(px[i].x), (int)nib_lo(px[i].y), (int)nib_hi(px[i].y)};
+            xop[par][i][1] = v4i{(int)nib_lo(px[i].z), (int)nib_hi(px[i].z), (int)nib_lo(px[i].w), (int)nib_hi(px[i].w)};
+        }
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
+            wop[par][j][0] = v4i{(int)nib_lo(pw[j].x), (int)nib_hi(pw[j].x), (int)nib_lo(pw[j].y), (int)nib_hi(pw[j].y)};
+            wop[par][j][1] = v4i{(int)nib_lo(pw[j].z), (int)nib_hi(pw[j].z), (int)nib_lo(pw[j].w), (int)nib_hi(pw[j].w)};
+        }
+    };
+    // One K64 step in issue order: MFMA m (h = m / 16, i = m / 4 % 4, j = m % 4) on buffer PAR, and from
+    // the 9th MFMA on (the first 8 cover the LDS latency of the pending fragments) the widening of
+    // 32 dwords spread over the remaining 24 MFMA shadows.  Scheduling barriers pin this order.
+    auto step_slot = [&](auto PAR, auto MI) {
+        constexpr int par = decltype(PAR)::value, m = decltype(MI)::value;
+        constexpr int h = m / 16, i = (m / 4) % 4, j = m % 4;
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop[par][j][h], xop[par][i][h], acc[i][j], 0, 0, 0);
+        if constexpr (m >= 8) {
+            constexpr int k = m - 8;   // 0..23 -> dwords [k*32/24, (k+1)*32/24)
+            widen_range(std::integral_constant<int, par ^ 1>{}, std::integral_constant<int, k * 32 / 24>{},
+                        std::integral_constant<int, (k + 1) * 32 / 24>{});
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto step = [&](auto PAR) {
+        __builtin_amdgcn_sched_barrier(0);
+#define CONVROT_SLOT(m) step_slot(PAR, std::integral_constant<int, m>{});
+        CONVROT_SLOT(0) CONVROT_SLOT(1) CONVROT_SLOT(2) CONVROT_SLOT(3) CONVROT_SLOT(4) CONVROT_SLOT(5)
+        CONVROT_SLOT(6) CONVROT_SLOT(7) CONVROT_SLOT(8) CONVROT_SLOT(9) CONVROT_SLOT(10) CONVROT_SLOT(11)
+        CONVROT_SLOT(12) CONVROT_SLOT(13) CONVROT_SLOT(14) CONVROT_SLOT(15) CONVROT_SLOT(16) CONVROT_SLOT(17)
+        CONVROT_SLOT(18) CONVROT_SLOT(19) CONVROT_SLOT(20) CONVROT_SLOT(21) CONVROT_SLOT(22) CONVROT_SLOT(23)
+        CONVROT_SLOT(24) CONVROT_SLOT(25) CONVROT_SLOT(26) CONVROT_SLOT(27) CONVROT_SLOT(28) CONVROT_SLOT(29)
+        CONVROT_SLOT(30) CONVROT_SLOT(31)
+#undef CONVROT_SLOT
+    };
+
+    // ---- pipeline: stages 0 .. S-2 are in flight before the loop.  With S >= 3 the block meets once per
+    // stage, just before its last K64 step: stage kt+1 must have landed by then (its first fragments are
+    // read right after), and the buffer stage kt-1 vacated is refilled with stage kt+S-1.  With S == 2 the
+    // refill is issued at the top of the stage and the block meets at its end.
+    static_assert(kSubSteps % 2 == 0, "operand double-buffer parity must return to 0 every stage");
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const int n = n0 + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4;
-                if (n >= N) continue;
-                if constexpr (RAW) {
+    for (int s = 0; s < kStages - 1; ++s) load_stage(s);
+    wait_vmcnt<(kStages - 2) * kChunksPerWave>();
+    __syncthreads();
+    read_frags(0, 0);
+    widen_all(std::integral_constant<int, 0>{});
+
+    // Steady state: every refill is a whole stage and a next stage exists, so the body is branch-free
+    // (one scheduling region per K64 step).  The last S-1 stages, and a ragged last stage, run the same
+    // steps through the general refill.
+    auto stage_iter = [&](int kt, auto FAST) {
+        constexpr bool fast = decltype(FAST)::value;
+        auto refill = [&](int st) {
+            if constexpr (fast) {
+                const uint32_t sl = wave_lds + (st % kStages) * kStageBytes;
+                const uint8_t *xb = xtile + (uint32_t)st * kRowBytes, *wb = wtile + (uint32_t)st * kRowBytes;
+#pragma unroll
+                for (int i = 0; i < kChunksPerWave; ++i)
+                    lds_dma16(i < kChunksPerWave / 2 ? xb : wb, goff[i], sl + i * 4096);
+            } else {
+                load_stage(st);
+            }
+        };
+        if constexpr (kStages == 2) refill(kt + 1);
+#pragma unroll
+        for (int ss = 0; ss < kSubSteps; ++ss) {
+            if (ss + 1 < kSubSteps) {
+                read_frags(kt, ss + 1);
+            } else if constexpr (kStages >= 3) {
+                wait_vmcnt<(kStages - 3) * kChunksPerWave>();
+                __syncthreads();
+                refill(kt + kStages - 1);
+                if (fast || kt + 1 < KT) read_frags(kt + 1, 0);
+            }
+            if (ss & 1) step(std::integral_constant<int, 1>{});
+            else step(std::integral_constant<int, 0>{});
+        }
+        if constexpr (kStages == 2) {
+            // S == 2 keeps no fragments across the barrier: the last step widened stale registers, redo
+            wait_vmcnt<0>();
+            __syncthreads();
+            if (fast || kt + 1 < KT) {
+                read_frags(kt + 1, 0);
+                widen_all(std::integral_constant<int, 0>{});
+            }
+        }
+    };
+    const int KT_fast = max(0, KT_full - (kStages - 1));
+    int kt = 0;
+    for (; kt < KT_fast; ++kt) stage_iter(kt, std::true_type{});
+    for (; kt < KT; ++kt) stage_iter(kt, std::false_type{});
+
+    // ---- epilogue.  Lane l, register r of a 32x32 tile: m = l % 32, n = 8 (r/4) + 4 (l/32) + r % 4.
+    wait_vmcnt<0>();         // drain the (unused) tail prefetches before their LDS buffers are reused
+    if constexpr (RAW) {
+        const bool vec_ok = (N & 3) == 0;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = m0 + wm0 + i * 32 + (lane & 31);
+            if (m >= M) continue;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const int n = n0 + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4;
+                    if (n >= N) continue;
                     int32_t o[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[e] = acc[i][j][rb * 4 + e] >> 8;
@@ -198,22 +362,55 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_w4a4_kernel(
                         for (int e = 0; e < 4; ++e)
                             if (n + e < N) dst[e] = o[e];
                     }
+                }
+            }
+        }
+    } else {
+        __syncthreads();     // every wavefront has finished reading the ring
+        uint8_t *stage = lds + wave * (32 * kEpiPitch);     // this wavefront's 32 x 128 bf16 staging tile
+        float swn[FN][4][4];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int n = n0 + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4 + e;
+                    swn[j][rb][e] = n < N ? w_scale[n] : 0.0f;
+                }
+        const bool vec_ok = (N & 7) == 0;
+        const int ncol = n0 + wn0 + (lane & 15) * 8;         // first of this lane's 8 output columns
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int mrow = m0 + wm0 + i * 32;
+            const int m = mrow + (lane & 31);
+            const float sxm = (m < M ? x_scale[m] : 0.0f) * 0.00390625f;   // 2^-8 undoes the 16 * 16 of the widening
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    float y[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) y[e] = ((float)acc[i][j][rb * 4 + e] * sxm) * swn[j][rb][e];
+                    const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
+                    *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
+                        make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+                }
+            // same wavefront reads back row-contiguous: 16 lanes cover one 256-byte row, 4 rows per pass
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int r = it * 4 + (lane >> 4);
+                const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + (lane & 15) * 16);
+                const int mo = mrow + r;
+                if (mo >= M || ncol >= N) continue;
+                uint16_t *dst = Y + (int64_t)mo * N + ncol;
+                if (vec_ok) {
+                    *reinterpret_cast<uint4 *>(dst) = v;
                 } else {
-                    uint16_t o[4];
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float swn = (n + e < N) ? w_scale[n + e] : 0.0f;
-                        o[e] = f32_to_bf16_rne(((float)acc[i][j][rb * 4 + e] * sxm) * swn);
-                    }
-                    uint16_t *dst = Y + (int64_t)m * N + n;
-                    if (vec_ok) {
-                        *reinterpret_cast<uint2 *>(dst) =
-                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (n + e < N) dst[e] = o[e];
-                    }
+                    for (int e = 0; e < 8; ++e)
+                        if (ncol + e < N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
                 }
             }
         }
@@ -222,34 +419,22 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_w4a4_kernel(
 
 namespace {
 
-template <int BM, int BN, int WGM, int WGN>
-hipError_t launch_tile(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, int M, int N,
-                       int K, void *Y, int32_t *acc, hipStream_t stream)
+template <bool RAW>
+hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, int M, int N, int K,
+                      void *Y, int32_t *acc, hipStream_t stream)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int ntiles = tiles_m * tiles_n;
     const int grid = ((ntiles + kNumXcd - 1) / kNumXcd) * kNumXcd;
-    const dim3 block(WGM * WGN * 64);
-    constexpr int lds_bytes = 2 * (BM + BN) * kLdsStride;
     static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4a4_kernel<BM, BN, WGM, WGN, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4a4_kernel<BM, BN, WGM, WGN, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4a4_kernel<RAW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    if (acc) {
-        hipLaunchKernelGGL((gemm_w4a4_kernel<BM, BN, WGM, WGN, true>), dim3(grid), block, lds_bytes, stream,
-                           (const uint8_t *)Xq, x_scale, (const uint8_t *)Wq, w_scale, M, N, K, (uint16_t *)nullptr,
-                           acc, tiles_m, tiles_n);
-    } else {
-        hipLaunchKernelGGL((gemm_w4a4_kernel<BM, BN, WGM, WGN, false>), dim3(grid), block, lds_bytes, stream,
-                           (const uint8_t *)Xq, x_scale, (const uint8_t *)Wq, w_scale, M, N, K, (uint16_t *)Y,
-                           (int32_t *)nullptr, tiles_m, tiles_n);
-    }
+    hipLaunchKernelGGL((gemm_w4a4_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsBytes, stream, (const uint8_t *)Xq,
+                       x_scale, (const uint8_t *)Wq, w_scale, M, N, K, (uint16_t *)Y, acc, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
@@ -260,7 +445,9 @@ hipError_t launch_gemm_w4a4(const void *Xq, const float *x_scale, const void *Wq
                             hipStream_t stream)
 {
     if (M == 0 || N == 0) return hipSuccess;
-    return launch_tile<256, 256, 2, 2>(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, Y_bf16, acc_i32, stream);
+    if (acc_i32)
+        return launch_one<true>(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, nullptr, acc_i32, stream);
+    return launch_one<false>(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, Y_bf16, nullptr, stream);
 }
 
 }  // namespace convrot
