@@ -18,9 +18,9 @@
 // lane's output address.  The 1/sqrt(g) = 2^-k normalisation is folded into the scale.
 //
 // Quantiser.  a = 2^-k max|z| (exact), s = a / 7 (IEEE division), r = 2^-k / s (IEEE division),
-// q = rne(z * r) taken by one fused multiply-add against 1.5 * 2^23, whose low mantissa bits are
-// then the two's-complement code.  |z r| <= 7 (1 + 2^-22), so no clamp is needed.  Rows whose
-// scale is a short dyadic number divide exactly instead (see the comment at the code).
+// q = rne(z / (2^k s)) decided exactly from two bracketing multiply-adds, with an exact-residual
+// fallback for the few wavefronts that hold a (near-)tie (see the comment at the code).
+// |z| / (2^k s) <= 7 (1 + 2^-22), so no clamp is needed.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -115,27 +115,36 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
     const bool row_ok = row < rows;
     const int units = K / kUnit;
 
-    float v[U][kUnit];
-    float amax = 0.0f;
-
+    // All loads are issued up front and unconditionally: a lane whose unit (or row) does not exist
+    // fetches the last unit of the last row instead and is masked out of the absmax and the stores.
+    // K % g == 0 makes a rotation group all-valid or all-invalid, so such lanes never feed valid ones.
+    const int64_t row_c = row_ok ? row : rows - 1;
+    const uint16_t *xrow = X + row_c * (int64_t)K;
+    u32x4 raw[U][2];
 #pragma unroll
     for (int i = 0; i < U; ++i) {
-        const int unit = i * T + t;
-        u32x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
-        if (row_ok && unit < units) {
-            const u32x4 *p = reinterpret_cast<const u32x4 *>(X + row * (int64_t)K + (int64_t)unit * kUnit);
-            lo = __builtin_nontemporal_load(p);
-            hi = __builtin_nontemporal_load(p + 1);
-        }
-        const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        const int unit = min(i * T + t, units - 1);
+        const u32x4 *p = reinterpret_cast<const u32x4 *>(xrow + (int64_t)unit * kUnit);
+        raw[i][0] = __builtin_nontemporal_load(p);
+        raw[i][1] = __builtin_nontemporal_load(p + 1);
+    }
+
+    float v[U][kUnit];
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const uint32_t w[8] = {raw[i][0].x, raw[i][0].y, raw[i][0].z, raw[i][0].w,
+                               raw[i][1].x, raw[i][1].y, raw[i][1].z, raw[i][1].w};
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             v[i][2 * j] = __uint_as_float(w[j] << 16);
             v[i][2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
         }
         rotate_unit<G>(v[i]);
+        float m = 0.0f;
 #pragma unroll
-        for (int e = 0; e < kUnit; ++e) amax = fmaxf(amax, fabsf(v[i][e]));
+        for (int e = 0; e < kUnit; ++e) m = fmaxf(m, fabsf(v[i][e]));
+        amax = (row_ok && i * T + t < units) ? fmaxf(amax, m) : amax;
     }
 
     // row absmax: wavefront butterfly, then across the row's wavefronts through LDS
@@ -157,33 +166,63 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
     const float r = norm / s;                          // IEEE division
     if (row_ok && t == 0) scale[row] = s;
 
-    // Codes.  Fast rows: one fma against 1.5 * 2^23 (ulp 1) rounds z * r to an integer, ties to even,
-    // and leaves the two's-complement code in the low mantissa bits.  r carries a relative error of
-    // 2^-24, which only matters when z / s is a half-integer to within ~1e-6.  On bf16-grid inputs
-    // that happens in bulk in exactly one situation: the row's absmax is a short multiple of 7, so
-    // that s itself is a short dyadic number and z = (n + 1/2) s is hit exactly.  Such rows (s has
-    // >= 8 trailing zero mantissa bits) take the correctly rounded division instead, which returns
-    // n + 1/2 exactly and lets the rounding see the tie.
-    constexpr float kMagic = 12582912.0f;
-    const bool short_scale = (__float_as_uint(s) & 0xFFu) == 0u;   // uniform over the row
+    // Codes.  q = rne(z / su) with su = s / norm, decided exactly although the lane only multiplies.
+    // r approximates 1 / su to 2^-24, so z / su lies strictly between z * r_lo and z * r_hi
+    // (r_lo, r_hi = r (1 -+ 2^-21)); rounding to an integer is monotonic, hence when both products
+    // round to the same integer so does the exact quotient.  One fused multiply-add against
+    // 1.5 * 2^23 + 8 rounds a product to nearest, ties to even, and leaves q + 8 (1..15, so no borrow
+    // out of the nibble) in the low mantissa bits.  A wavefront in which any pair disagrees (a few
+    // in a thousand on random data; every exact tie, which bf16-grid inputs do produce when the
+    // scale is a short dyadic number) redoes its codes through the exact residual
+    // e = z - q su (one rounding of a quantity that is representable whenever q is the nearest or
+    // a neighbouring integer), which decides the rounding, ties to even, without a division.
+    constexpr float kMagic = 12582912.0f + 8.0f;
+    constexpr uint32_t kMagicBits = 0x4B400008u;
     const float su = s / norm;                                      // scale in un-normalised units (exact)
+    const float r_lo = r * (1.0f - 0x1p-21f), r_hi = r * (1.0f + 0x1p-21f);
+    const float half_su = 0.5f * su;
     const int tf = t ^ lane_flip_mask<G>();
 #pragma unroll
     for (int i = 0; i < U; ++i) {
-        uint32_t d0 = 0, d1 = 0;
-        if (short_scale) {
+        uint32_t disagree = 0;
+        uint32_t code[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                d0 |= ((uint32_t)(int)rintf(v[i][e] / su) & 0xFu) << (4 * e);
-                d1 |= ((uint32_t)(int)rintf(v[i][e + 8] / su) & 0xFu) << (4 * e);
+        for (int hlf = 0; hlf < 2; ++hlf) {
+            // Horner in base 16 over the raw float bits: sum_e (C + u_e) 16^e mod 2^32, C the magic's bits
+            // (the same sum over the other bracket: digits differ by at most one, so the two sums are
+            // equal exactly when every pair of codes is)
+            uint32_t acc = 0, acc_hi = 0;
+#pragma unroll
+            for (int e = 7; e >= 0; --e) {
+                const float z = v[i][8 * hlf + e];
+                acc = (acc << 4) + __float_as_uint(fmaf(z, r_lo, kMagic));
+                acc_hi = (acc_hi << 4) + __float_as_uint(fmaf(z, r_hi, kMagic));
             }
-        } else {
+            disagree |= acc ^ acc_hi;
+            // remove sum_e (C - 8) 16^e (only e = 0, 1, 2 survive mod 2^32), then offset-binary
+            // nibbles -> two's complement
+            constexpr uint32_t kBias = (kMagicBits - 8u) + ((kMagicBits - 8u) << 4) + ((kMagicBits - 8u) << 8);
+            code[hlf] = (acc - kBias) ^ 0x88888888u;
+        }
+        if (__builtin_amdgcn_ballot_w64(disagree != 0) != 0) {   // wavefront-uniform, rare
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                d0 |= (__float_as_uint(fmaf(v[i][e], r, kMagic)) & 0xFu) << (4 * e);
-                d1 |= (__float_as_uint(fmaf(v[i][e + 8], r, kMagic)) & 0xFu) << (4 * e);
+            for (int hlf = 0; hlf < 2; ++hlf) {
+                uint32_t d = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float z = v[i][8 * hlf + e];
+                    float q = rintf(z * r);
+                    const float res = fmaf(-q, su, z);
+                    const bool odd = ((int)q & 1) != 0;
+                    const bool up = res > half_su || (res == half_su && odd);
+                    const bool dn = res < -half_su || (res == -half_su && odd);
+                    q += (up ? 1.0f : 0.0f) - (dn ? 1.0f : 0.0f);
+                    d |= ((uint32_t)(int)q & 0xFu) << (4 * e);
+                }
+                code[hlf] = d;
             }
         }
+        const uint32_t d0 = code[0], d1 = code[1];
         const int unit = i * T + tf;
         if (row_ok && unit < units) {
             u32x2 *o = reinterpret_cast<u32x2 *>(Xq + row * (int64_t)(K / 2) + (int64_t)unit * (kUnit / 2));
