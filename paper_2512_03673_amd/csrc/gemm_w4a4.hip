@@ -57,7 +57,8 @@ constexpr int kStages = CONVROT_GEMM_STAGES;
 constexpr int kPieces = kRowBytes / 16;                   // 16-byte pieces per LDS row
 constexpr int kSubSteps = kRowBytes / 32;                 // K64 steps (one ds_read_b128 per fragment) per stage
 constexpr int kStageBytes = (BM + BN) * kRowBytes;
-constexpr int kLdsBytes = kStages * kStageBytes;          // 128 KB
+constexpr int kLdsBytes = kStages * kStageBytes;          // the ring: 128 KB
+constexpr int kLdsTotal = kLdsBytes + (BM + BN) * 4;      // + the tile's dequantisation scales
 constexpr int kChunksPerWave = kStageBytes / 1024 / 4;    // 1 KB LDS-direct loads per wavefront per stage
 constexpr int kRowsPerChunk = 1024 / kRowBytes;
 constexpr int kEpiPitch = WTN * 2 + 16;                   // bf16 row of the wavefront tile + pad
@@ -66,7 +67,7 @@ constexpr int kNumXcd = 8;
 static_assert(kRowBytes == 64 || kRowBytes == 128, "row bytes");
 static_assert(kChunksPerWave * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
 static_assert(4 * 32 * kEpiPitch <= kLdsBytes, "epilogue staging must fit the ring");
-static_assert(kLdsBytes <= 160 * 1024, "LDS");
+static_assert(kLdsTotal <= 160 * 1024, "LDS");
 
 // 16 zero bytes for LDS-direct loads that fall past the end of K.
 __device__ const uint4 kZeroPiece = {0u, 0u, 0u, 0u};
@@ -167,25 +168,23 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
     const uint32_t wave_lds = lds_base + __builtin_amdgcn_readfirstlane(wave) * 1024;
     const int KT_full = Kb / kRowBytes;
-    auto load_stage = [&](int kt) {
-        const uint32_t sl = wave_lds + (kt % kStages) * kStageBytes;   // chunk wave + 4 i sits 4096 i further on
+    // chunk i (0 .. kChunksPerWave-1) of this wavefront's share of stage kt; chunk wave + 4 i sits 4096 i further on
+    auto load_chunk_fast = [&](int kt, int i) {     // kt < KT_full: a whole stage inside K
+        const uint32_t sl = wave_lds + (kt % kStages) * kStageBytes;
+        const uint32_t koff = (uint32_t)kt * kRowBytes;
+        lds_dma16((i < kChunksPerWave / 2 ? xtile : wtile) + koff, goff[i], sl + i * 4096);
+    };
+    auto load_chunk = [&](int kt, int i) {
+        const uint32_t sl = wave_lds + (kt % kStages) * kStageBytes;
         const uint32_t koff = (uint32_t)kt * kRowBytes;
         if (kt < KT_full) {
-            const uint8_t *xb = xtile + koff, *wb = wtile + koff;
-#pragma unroll
-            for (int i = 0; i < kChunksPerWave; ++i)
-                lds_dma16(i < kChunksPerWave / 2 ? xb : wb, goff[i], sl + i * 4096);
+            lds_dma16((i < kChunksPerWave / 2 ? xtile : wtile) + koff, goff[i], sl + i * 4096);
         } else if (kt < KT) {   // ragged last stage: pieces past the end of K come from a zero constant
-#pragma unroll
-            for (int i = 0; i < kChunksPerWave; ++i) {
-                const uint8_t *g = (i < kChunksPerWave / 2 ? xtile : wtile) + (goff[i] + koff);
-                if ((int)koff + gcol[i] >= Kb) g = reinterpret_cast<const uint8_t *>(&kZeroPiece);
-                lds_dma16_addr(g, sl + i * 4096);
-            }
+            const uint8_t *g = (i < kChunksPerWave / 2 ? xtile : wtile) + (goff[i] + koff);
+            if ((int)koff + gcol[i] >= Kb) g = reinterpret_cast<const uint8_t *>(&kZeroPiece);
+            lds_dma16_addr(g, sl + i * 4096);
         } else {                // past the end: a dummy fill keeps the vmcnt bookkeeping uniform
-#pragma unroll
-            for (int i = 0; i < kChunksPerWave; ++i)
-                lds_dma16_addr(reinterpret_cast<const uint8_t *>(&kZeroPiece), sl + i * 4096);
+            lds_dma16_addr(reinterpret_cast<const uint8_t *>(&kZeroPiece), sl + i * 4096);
         }
     };
 
@@ -199,12 +198,12 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
     const int wslab = (BM + wn0) * kRowBytes;
 
     uint4 px[FM], pw[FN];
-    auto read_frags = [&](int kt, int ks) {
+    // fragment f of K64 step ks of stage kt: f < FM is X rows 32 f .., otherwise W rows 32 (f - FM) ..
+    auto read_frag = [&](int kt, int ks, auto F) {
+        constexpr int f = decltype(F)::value;
         const uint8_t *sbase = lds + (kt % kStages) * kStageBytes + foff[ks];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) px[i] = *reinterpret_cast<const uint4 *>(sbase + xslab + i * 32 * kRowBytes);
-#pragma unroll
-        for (int j = 0; j < FN; ++j) pw[j] = *reinterpret_cast<const uint4 *>(sbase + wslab + j * 32 * kRowBytes);
+        if constexpr (f < FM) px[f] = *reinterpret_cast<const uint4 *>(sbase + xslab + f * 32 * kRowBytes);
+        else pw[f - FM] = *reinterpret_cast<const uint4 *>(sbase + wslab + (f - FM) * 32 * kRowBytes);
     };
 
     v16i acc[FM][FN];
@@ -215,8 +214,8 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // Widened operands are double-buffered: while the 32 MFMAs of one K64 step run, the VALU widens
-    // the fragments of the next step in their shadow (3 VALU operations per packed dword, 96 per step).
+    // Widened operands are double-buffered: while the 32 MFMAs of one K64 step run, the fragments of the
+    // next step are fetched from LDS and widened in their shadow (3 VALU operations per packed dword).
     v4i xop[2][FM][2], wop[2][FN][2];
     // widen packed dword number d (0..31) of the pending fragments into buffer PAR:
     // fragment d / 4 (0-3: X rows, 4-7: W rows), dword d % 4 -> operand half (d % 4) / 2, bytes 8 (d % 2)..
@@ -242,25 +241,32 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
         }
     };
     auto widen_all = [&](auto PAR) {
-        constexpr int par = decltype(PAR)::value;
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            xop[par][i][0] = v4i{(int)nib_lo(px[i].x), (int)nib_hi(px[i].x), (int)nib_lo(px[i].y), (int)nib_hi(px[i].y)};
-            xop[par][i][1] = v4i{(int)nib_lo(px[i].z), (int)nib_hi(px[i].z), (int)nib_lo(px[i].w), (int)nib_hi(px[i].w)};
-        }
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            wop[par][j][0] = v4i{(int)nib_lo(pw[j].x), (int)nib_hi(pw[j].x), (int)nib_lo(pw[j].y), (int)nib_hi(pw[j].y)};
-            wop[par][j][1] = v4i{(int)nib_lo(pw[j].z), (int)nib_hi(pw[j].z), (int)nib_lo(pw[j].w), (int)nib_hi(pw[j].w)};
-        }
+#define CONVROT_W(d) widen_dword(PAR, std::integral_constant<int, d>{});
+        CONVROT_W(0) CONVROT_W(1) CONVROT_W(2) CONVROT_W(3) CONVROT_W(4) CONVROT_W(5) CONVROT_W(6) CONVROT_W(7)
+        CONVROT_W(8) CONVROT_W(9) CONVROT_W(10) CONVROT_W(11) CONVROT_W(12) CONVROT_W(13) CONVROT_W(14) CONVROT_W(15)
+        CONVROT_W(16) CONVROT_W(17) CONVROT_W(18) CONVROT_W(19) CONVROT_W(20) CONVROT_W(21) CONVROT_W(22) CONVROT_W(23)
+        CONVROT_W(24) CONVROT_W(25) CONVROT_W(26) CONVROT_W(27) CONVROT_W(28) CONVROT_W(29) CONVROT_W(30) CONVROT_W(31)
+#undef CONVROT_W
     };
-    // One K64 step in issue order: MFMA m (h = m / 16, i = m / 4 % 4, j = m % 4) on buffer PAR, and from
-    // the 9th MFMA on (the first 8 cover the LDS latency of the pending fragments) the widening of
-    // 32 dwords spread over the remaining 24 MFMA shadows.  Scheduling barriers pin this order.
-    auto step_slot = [&](auto PAR, auto MI) {
-        constexpr int par = decltype(PAR)::value, m = decltype(MI)::value;
+
+    // One K64 step, slot by slot, in issue order.  A wavefront issues in order and is alone on its SIMD,
+    // so whatever stalls at issue (a burst of LDS reads or of LDS-direct loads queueing up, a barrier)
+    // idles the MFMA pipe; every memory instruction therefore gets an MFMA slot of its own.  Slot m:
+    //   MFMA m (h = m / 16, i = m / 4 % 4, j = m % 4) on operand buffer PAR
+    //   m < 8        ds_read of fragment m of the next step (stage nkt, K64 step nks)
+    //   8 <= m < 16  LDS-direct load of chunk m - 8 of stage rst (MODE kRefillFast / kRefillAny)
+    //   m >= 8       widening of the fetched fragments into buffer PAR ^ 1, 32 dwords over 24 slots
+    // Scheduling barriers pin this order.
+    constexpr int kNoSync = 0, kRefillFast = 1, kRefillAny = 2, kDrain = 3;
+    auto step_slot = [&](auto PAR, auto MI, auto MODE, int nkt, int nks, int rst) {
+        constexpr int par = decltype(PAR)::value, m = decltype(MI)::value, mode = decltype(MODE)::value;
         constexpr int h = m / 16, i = (m / 4) % 4, j = m % 4;
         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop[par][j][h], xop[par][i][h], acc[i][j], 0, 0, 0);
+        if constexpr (m < FM + FN) read_frag(nkt, nks, std::integral_constant<int, m>{});
+        if constexpr (m >= 8 && m - 8 < kChunksPerWave) {
+            if constexpr (mode == kRefillFast) load_chunk_fast(rst, m - 8);
+            if constexpr (mode == kRefillAny) load_chunk(rst, m - 8);
+        }
         if constexpr (m >= 8) {
             constexpr int k = m - 8;   // 0..23 -> dwords [k*32/24, (k+1)*32/24)
             widen_range(std::integral_constant<int, par ^ 1>{}, std::integral_constant<int, k * 32 / 24>{},
@@ -268,9 +274,23 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto step = [&](auto PAR) {
+    // Except with kNoSync the step opens with the wait for stage nkt (this wavefront's share of it:
+    // LDS-direct loads retire in order, `behind` later stages may still be in flight) and the block
+    // barrier that extends the guarantee to everybody's share.
+    auto step = [&](auto PAR, auto MODE, int nkt, int nks, int rst, int behind) {
+        constexpr int mode = decltype(MODE)::value;
         __builtin_amdgcn_sched_barrier(0);
-#define CONVROT_SLOT(m) step_slot(PAR, std::integral_constant<int, m>{});
+        if constexpr (mode != kNoSync) {
+            if constexpr (mode == kDrain) {
+                if (behind >= 1 && kStages > 3) wait_vmcnt<(kStages > 3 ? 1 : 0) * kChunksPerWave>();
+                else wait_vmcnt<0>();
+            } else {
+                wait_vmcnt<(kStages - 3) * kChunksPerWave>();
+            }
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#define CONVROT_SLOT(m) step_slot(PAR, std::integral_constant<int, m>{}, MODE, nkt, nks, rst);
         CONVROT_SLOT(0) CONVROT_SLOT(1) CONVROT_SLOT(2) CONVROT_SLOT(3) CONVROT_SLOT(4) CONVROT_SLOT(5)
         CONVROT_SLOT(6) CONVROT_SLOT(7) CONVROT_SLOT(8) CONVROT_SLOT(9) CONVROT_SLOT(10) CONVROT_SLOT(11)
         CONVROT_SLOT(12) CONVROT_SLOT(13) CONVROT_SLOT(14) CONVROT_SLOT(15) CONVROT_SLOT(16) CONVROT_SLOT(17)
@@ -280,62 +300,58 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
 #undef CONVROT_SLOT
     };
 
-    // ---- pipeline: stages 0 .. S-2 are in flight before the loop.  With S >= 3 the block meets once per
-    // stage, just before its last K64 step: stage kt+1 must have landed by then (its first fragments are
-    // read right after), and the buffer stage kt-1 vacated is refilled with stage kt+S-1.  With S == 2 the
-    // refill is issued at the top of the stage and the block meets at its end.
+    // ---- dequantisation scales of the tile's 256 rows and 256 columns: thread t fetches x_scale[m0 + t]
+    // and w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
+    // the ring) once the loop is over.  x_scale carries the 2^-8 that undoes the 16 * 16 of the widening.
+    float my_sx = 0.0f, my_sw = 0.0f;
+    if constexpr (!RAW) {
+        if (m0 + tid < M) my_sx = x_scale[m0 + tid] * 0.00390625f;
+        if (n0 + tid < N) my_sw = w_scale[n0 + tid];
+    }
+
+    // ---- pipeline: stages 0 .. S-2 are in flight before the loop (stages past the end of K are dummy
+    // fills, so that the count of loads in flight does not depend on K).  The block meets once per
+    // stage, at the start of the stage's last K64 step: stage kt+1 must have landed by then (its first
+    // fragments are fetched during that step), and the buffer stage kt-1 vacated is refilled with
+    // stage kt+S-1.
+    static_assert(kStages == 3 || kStages == 4, "wait counts below are written for 3 or 4 stages");
     static_assert(kSubSteps % 2 == 0, "operand double-buffer parity must return to 0 every stage");
+    static_assert(kChunksPerWave <= 24 && FM + FN == 8, "slot plan of a K64 step");
 #pragma unroll
-    for (int s = 0; s < kStages - 1; ++s) load_stage(s);
+    for (int s = 0; s < kStages - 1; ++s)
+#pragma unroll
+        for (int i = 0; i < kChunksPerWave; ++i) load_chunk(s, i);
     wait_vmcnt<(kStages - 2) * kChunksPerWave>();
     __syncthreads();
-    read_frags(0, 0);
+#define CONVROT_F(f) read_frag(0, 0, std::integral_constant<int, f>{});
+    CONVROT_F(0) CONVROT_F(1) CONVROT_F(2) CONVROT_F(3) CONVROT_F(4) CONVROT_F(5) CONVROT_F(6) CONVROT_F(7)
+#undef CONVROT_F
     widen_all(std::integral_constant<int, 0>{});
 
-    // Steady state: every refill is a whole stage and a next stage exists, so the body is branch-free
-    // (one scheduling region per K64 step).  The last S-1 stages, and a ragged last stage, run the same
-    // steps through the general refill.
-    auto stage_iter = [&](int kt, auto FAST) {
-        constexpr bool fast = decltype(FAST)::value;
-        auto refill = [&](int st) {
-            if constexpr (fast) {
-                const uint32_t sl = wave_lds + (st % kStages) * kStageBytes;
-                const uint8_t *xb = xtile + (uint32_t)st * kRowBytes, *wb = wtile + (uint32_t)st * kRowBytes;
-#pragma unroll
-                for (int i = 0; i < kChunksPerWave; ++i)
-                    lds_dma16(i < kChunksPerWave / 2 ? xb : wb, goff[i], sl + i * 4096);
-            } else {
-                load_stage(st);
-            }
-        };
-        if constexpr (kStages == 2) refill(kt + 1);
+    // Three kinds of stage: the steady state refills a whole stage inside K (branch-free body); at
+    // most one stage refills the ragged last stage of K through the general loader; the last S-1
+    // stages refill nothing and only drain (their fetches past the last stage read a ring buffer
+    // whose contents are never used).
+    auto stage_iter = [&](int kt, auto MODE) {
+        const int last_issued = max(KT - 1, kStages - 2);
+        const int behind = min(kt + kStages - 2, last_issued) - (kt + 1);   // stages in flight behind kt+1
 #pragma unroll
         for (int ss = 0; ss < kSubSteps; ++ss) {
             if (ss + 1 < kSubSteps) {
-                read_frags(kt, ss + 1);
-            } else if constexpr (kStages >= 3) {
-                wait_vmcnt<(kStages - 3) * kChunksPerWave>();
-                __syncthreads();
-                refill(kt + kStages - 1);
-                if (fast || kt + 1 < KT) read_frags(kt + 1, 0);
-            }
-            if (ss & 1) step(std::integral_constant<int, 1>{});
-            else step(std::integral_constant<int, 0>{});
-        }
-        if constexpr (kStages == 2) {
-            // S == 2 keeps no fragments across the barrier: the last step widened stale registers, redo
-            wait_vmcnt<0>();
-            __syncthreads();
-            if (fast || kt + 1 < KT) {
-                read_frags(kt + 1, 0);
-                widen_all(std::integral_constant<int, 0>{});
+                if (ss & 1) step(std::integral_constant<int, 1>{}, std::integral_constant<int, kNoSync>{}, kt, ss + 1, 0, 0);
+                else step(std::integral_constant<int, 0>{}, std::integral_constant<int, kNoSync>{}, kt, ss + 1, 0, 0);
+            } else {
+                if (ss & 1) step(std::integral_constant<int, 1>{}, MODE, kt + 1, 0, kt + kStages - 1, behind);
+                else step(std::integral_constant<int, 0>{}, MODE, kt + 1, 0, kt + kStages - 1, behind);
             }
         }
     };
-    const int KT_fast = max(0, KT_full - (kStages - 1));
+    const int KT_fast = max(0, KT_full - (kStages - 1));     // stages whose refill is a whole stage inside K
+    const int KT_refill = max(0, KT - (kStages - 1));        // stages that refill anything at all
     int kt = 0;
-    for (; kt < KT_fast; ++kt) stage_iter(kt, std::true_type{});
-    for (; kt < KT; ++kt) stage_iter(kt, std::false_type{});
+    for (; kt < KT_fast; ++kt) stage_iter(kt, std::integral_constant<int, kRefillFast>{});
+    for (; kt < KT_refill; ++kt) stage_iter(kt, std::integral_constant<int, kRefillAny>{});
+    for (; kt < KT; ++kt) stage_iter(kt, std::integral_constant<int, kDrain>{});
 
     // ---- epilogue.  Lane l, register r of a 32x32 tile: m = l % 32, n = 8 (r/4) + 4 (l/32) + r % 4.
     wait_vmcnt<0>();         // drain the (unused) tail prefetches before their LDS buffers are reused
@@ -366,54 +382,66 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
             }
         }
     } else {
-        __syncthreads();     // every wavefront has finished reading the ring
-        uint8_t *stage = lds + wave * (32 * kEpiPitch);     // this wavefront's 32 x 128 bf16 staging tile
-        float swn[FN][4][4];
+        float *sx_lds = reinterpret_cast<float *>(lds + kLdsBytes), *sw_lds = sx_lds + BM;
+        sx_lds[tid] = my_sx;
+        sw_lds[tid] = my_sw;
+        __syncthreads();     // every wavefront has finished reading the ring; the scales are visible
+        // `interior`: the tile lies wholly inside Y and rows of Y are 16-byte multiples, so the stores need
+        // no bounds checks (uniform over the block).
+        const bool interior = m0 + BM <= M && n0 + BN <= N && (N & 7) == 0;
+        // lane l, register r of a 32x32 accumulator tile: m = l % 32, n = 8 (r / 4) + 4 (l / 32) + r % 4
+        float swn[FN][4][4], sxm[FM];
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb)
+            for (int rb = 0; rb < 4; ++rb) {
+                const float4 v = *reinterpret_cast<const float4 *>(sw_lds + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4);
+                swn[j][rb][0] = v.x; swn[j][rb][1] = v.y; swn[j][rb][2] = v.z; swn[j][rb][3] = v.w;
+            }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int n = n0 + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4 + e;
-                    swn[j][rb][e] = n < N ? w_scale[n] : 0.0f;
-                }
-        const bool vec_ok = (N & 7) == 0;
+        for (int i = 0; i < FM; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
+        uint8_t *stage = lds + wave * (32 * kEpiPitch);     // this wavefront's 32 x 128 bf16 staging tile
         const int ncol = n0 + wn0 + (lane & 15) * 8;         // first of this lane's 8 output columns
+        auto body = [&](auto INTERIOR) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int mrow = m0 + wm0 + i * 32;
-            const int m = mrow + (lane & 31);
-            const float sxm = (m < M ? x_scale[m] : 0.0f) * 0.00390625f;   // 2^-8 undoes the 16 * 16 of the widening
+            for (int i = 0; i < FM; ++i) {
+                const int mrow = m0 + wm0 + i * 32;
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+                for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int rb = 0; rb < 4; ++rb) {
-                    float y[4];
+                    for (int rb = 0; rb < 4; ++rb) {
+                        float y[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) y[e] = ((float)acc[i][j][rb * 4 + e] * sxm) * swn[j][rb][e];
-                    const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
-                    *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
-                        make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
-                }
-            // same wavefront reads back row-contiguous: 16 lanes cover one 256-byte row, 4 rows per pass
+                        for (int e = 0; e < 4; ++e) y[e] = ((float)acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
+                        const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
+                        *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
+                            make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+                    }
+                // same wavefront reads back row-contiguous: 16 lanes cover one 256-byte row, 4 rows per pass
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int r = it * 4 + (lane >> 4);
-                const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + (lane & 15) * 16);
-                const int mo = mrow + r;
-                if (mo >= M || ncol >= N) continue;
-                uint16_t *dst = Y + (int64_t)mo * N + ncol;
-                if (vec_ok) {
-                    *reinterpret_cast<uint4 *>(dst) = v;
-                } else {
-                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                for (int it = 0; it < 8; ++it) {
+                    const int r = it * 4 + (lane >> 4);
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + (lane & 15) * 16);
+                    const int mo = mrow + r;
+                    uint16_t *dst = Y + (int64_t)mo * N + ncol;
+                    if constexpr (decltype(INTERIOR)::value) {
+                        *reinterpret_cast<uint4 *>(dst) = v;
+                    } else {
+                        if (mo >= M || ncol >= N) continue;
+                        if ((N & 7) == 0) {
+                            *reinterpret_cast<uint4 *>(dst) = v;
+                        } else {
+                            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (ncol + e < N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                            for (int e = 0; e < 8; ++e)
+                                if (ncol + e < N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                        }
+                    }
                 }
             }
-        }
+        };
+        if (interior) body(std::true_type{});
+        else body(std::false_type{});
     }
 }
 
@@ -429,11 +457,11 @@ hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, cons
     static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4a4_kernel<RAW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((gemm_w4a4_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsBytes, stream, (const uint8_t *)Xq,
+    hipLaunchKernelGGL((gemm_w4a4_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsTotal, stream, (const uint8_t *)Xq,
                        x_scale, (const uint8_t *)Wq, w_scale, M, N, K, (uint16_t *)Y, acc, tiles_m, tiles_n);
     return hipGetLastError();
 }
