@@ -14,124 +14,65 @@
 // (|256 acc| <= 256 * 49 * K < 2^31 for K <= 65536) and the factor 2^-8 is folded, exactly,
 // into the epilogue.
 //
-// Data movement.  A block owns a 256 x 256 output tile (4 wavefronts, 128 x 128 each, 256
-// accumulator registers per lane).  Packed codes travel HBM -> LDS with global_load_lds_dwordx4
-// (no register staging) into a ring of 4 stages of 128 codes (64 bytes) of K; the codes stay
-// packed in LDS and are widened in registers after ds_read_b128, 3 VALU operations per MFMA.
-// LDS rows are 64 bytes; the four 16-byte pieces of a row are XOR-swizzled by row so that the
-// fragment reads (32 consecutive rows, one piece) touch every bank once.  The swizzle is applied
-// on the global side: an LDS-direct load writes lane l at base + 16 l, so lane l simply fetches
-// the piece that belongs there.
+// Data movement.  A block owns a 256 x 128 output tile (4 wavefronts, 128 x 64 each, 128
+// accumulator registers per lane) and needs 256 registers per lane and 74 KB of LDS, so that two
+// blocks share a compute unit: while one runs its prologue or epilogue, or waits at a barrier,
+// the other keeps the MFMA pipe busy.  Packed codes travel HBM -> LDS with
+// global_load_lds_dwordx4 (no register staging) into a ring of 3 stages of 128 codes (64 bytes)
+// of K; the codes stay packed in LDS and are widened in registers after ds_read_b128, 3 VALU
+// operations per packed dword.  LDS rows are 64 bytes; the four 16-byte pieces of a row are
+// XOR-swizzled by row so that the fragment reads (32 consecutive rows, one piece) touch every
+// bank once.  The swizzle is applied on the global side: an LDS-direct load writes lane l at
+// base + 16 l, so lane l simply fetches the piece that belongs there.
 //
 // The MFMA's row operand is the W tile and its column operand the X tile, so that a lane ends up
 // with four consecutive n for one m; the epilogue scales, rounds to bf16, transposes through LDS
-// and writes 16 bytes per lane, 256 contiguous bytes per output row.
-#include <hip/hip_runtime.h>
-#include <stdint.h>
-
-#include <type_traits>
+// and writes 16 bytes per lane, 128 contiguous bytes per output row.
+//
+// This kernel takes K % 128 == 0 (every stage of the ring whole); other K go to the kernel in
+// gemm_w4a4_generic.hip.
+#include "gemm_w4a4_common.h"
 
 #include "convrot_internal.h"
 
 namespace convrot {
 
+using gemm::kNumXcd;
+using gemm::kRowBytes;
+using gemm::kSubSteps;
+using gemm::lds_dma16;
+using gemm::nib_hi;
+using gemm::nib_lo;
+using gemm::pack_bf16x2;
+using gemm::swz;
+using gemm::tile_of_block;
+using gemm::v16i;
+using gemm::v4i;
+using gemm::wait_vmcnt;
+
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v2f __attribute__((ext_vector_type(2)));
-typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-
-constexpr int BM = 256, BN = 256;        // block tile
-constexpr int kThreads = 256;            // 4 wavefronts, 2 x 2
-constexpr int WTM = 128, WTN = 128;      // wavefront tile
-constexpr int FM = WTM / 32, FN = WTN / 32;
-#ifndef CONVROT_GEMM_ROW_BYTES
-#define CONVROT_GEMM_ROW_BYTES 64
-#endif
-#ifndef CONVROT_GEMM_STAGES
-#define CONVROT_GEMM_STAGES 4
-#endif
-constexpr int kRowBytes = CONVROT_GEMM_ROW_BYTES;         // packed bytes of K per row per stage (64 B = 128 codes)
-constexpr int kStages = CONVROT_GEMM_STAGES;
-constexpr int kPieces = kRowBytes / 16;                   // 16-byte pieces per LDS row
-constexpr int kSubSteps = kRowBytes / 32;                 // K64 steps (one ds_read_b128 per fragment) per stage
-constexpr int kStageBytes = (BM + BN) * kRowBytes;
-constexpr int kLdsBytes = kStages * kStageBytes;          // the ring: 128 KB
-constexpr int kLdsTotal = kLdsBytes + (BM + BN) * 4;      // + the tile's dequantisation scales
-constexpr int kChunksPerWave = kStageBytes / 1024 / 4;    // 1 KB LDS-direct loads per wavefront per stage
-constexpr int kRowsPerChunk = 1024 / kRowBytes;
-constexpr int kEpiPitch = WTN * 2 + 16;                   // bf16 row of the wavefront tile + pad
-constexpr int kNumXcd = 8;
-
-static_assert(kRowBytes == 64 || kRowBytes == 128, "row bytes");
-static_assert(kChunksPerWave * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
-static_assert(4 * 32 * kEpiPitch <= kLdsBytes, "epilogue staging must fit the ring");
-static_assert(kLdsTotal <= 160 * 1024, "LDS");
-
-// 16 zero bytes for LDS-direct loads that fall past the end of K.
-__device__ const uint4 kZeroPiece = {0u, 0u, 0u, 0u};
-
-__device__ __forceinline__ uint32_t nib_lo(uint32_t p) { return (p << 4) & 0xF0F0F0F0u; }
-__device__ __forceinline__ uint32_t nib_hi(uint32_t p) { return p & 0xF0F0F0F0u; }
-
-// Which of the four 16-byte slots of its LDS row a piece lands in: slot = piece ^ swz(row).
-// For any 8 consecutive rows the (row & 1, slot) pairs are distinct (32 banks), and for any 16
-// consecutive rows the (row & 3, slot) pairs are distinct (64 banks).
-__device__ __forceinline__ int swz(int row)
-{
-    if constexpr (kPieces == 4) return ((row >> 1) ^ (row >> 3)) & 3;
-    else return (row ^ (row >> 3)) & 7;
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    // gfx9 encoding: vmcnt = {imm[15:14], imm[3:0]}, expcnt = imm[6:4], lgkmcnt = imm[11:8]
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
-}
-
-// global_load_lds_dwordx4: lane l copies 16 bytes from its global address to LDS address M0 + 16 l.
-__device__ __forceinline__ void lds_dma16(const uint8_t *base, uint32_t lane_off, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory");
-}
-__device__ __forceinline__ void lds_dma16_addr(const uint8_t *lane_ptr, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(lane_ptr), "s"(lds_addr) : "memory");
-}
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
-{
-    v2bf r = __builtin_convertvector((v2f){a, b}, v2bf);   // v_cvt_pk_bf16_f32: round to nearest even
-    return *reinterpret_cast<uint32_t *>(&r);
-}
-
-// Tile order: blocks are dealt round-robin to the 8 XCDs by the hardware, each XCD has its own
-// L2.  Give every XCD one contiguous range of logical tile ids, and walk that range in bands of
-// `GM` tile rows so that tiles that run together share X and W panels.
-__device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n, int &tm, int &tn)
-{
-    const int ntiles = tiles_m * tiles_n;
-    const int per_xcd = (ntiles + kNumXcd - 1) / kNumXcd;
-    const int id = (bid % kNumXcd) * per_xcd + bid / kNumXcd;
-    if (id >= ntiles) return false;
-    constexpr int GM = 6;
-    const int band = id / (GM * tiles_n);
-    const int first_m = band * GM;
-    const int rows_in_band = min(GM, tiles_m - first_m);
-    const int local = id - band * GM * tiles_n;
-    tm = first_m + local % rows_in_band;
-    tn = local / rows_in_band;
-    return true;
-}
+constexpr int kThreads = 256;                 // 4 wavefronts, 2 x 2
+constexpr int TM = 256, TN = 128;             // block tile
+constexpr int WM = 128, WN = 64;              // wavefront tile
+constexpr int XF = WM / 32, WF = WN / 32;     // fragments (32 rows x one K64 step) per wavefront: 4 of X, 2 of W
+constexpr int NF = XF + WF;
+constexpr int kStages = 3;
+constexpr int kStageBytes = (TM + TN) * kRowBytes;        // 24 KB
+constexpr int kRingBytes = kStages * kStageBytes;         // 72 KB
+constexpr int kChunks = kStageBytes / 1024 / 4;           // 1 KB LDS-direct loads per wavefront per stage: 6
+constexpr int kXChunks = TM * kRowBytes / 1024 / 4;       // ... of which the first 4 fetch X rows
+constexpr int kEpiPitch = WN * 2 + 16;                    // bf16 row of the wavefront tile + pad
+constexpr int kLdsTotal = kRingBytes + (TM + TN) * 4;     // + the tile's dequantisation scales
+static_assert(kChunks * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
+static_assert(4 * 32 * kEpiPitch <= kRingBytes, "epilogue staging must fit the ring");
+static_assert(2 * kLdsTotal <= 160 * 1024, "two blocks per compute unit");
+static_assert(kSubSteps == 2 && NF == 6, "slot plan of a K64 step");
 
 }  // namespace
 
 template <bool RAW>
-__global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
+__global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ x_scale, const uint8_t *__restrict__ Wq,
     const float *__restrict__ w_scale, int M, int N, int K, uint16_t *__restrict__ Y,
     int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
@@ -140,52 +81,41 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
 
     int tm, tn;
     if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int m0 = tm * TM, n0 = tn * TN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave & 1) * WTM, wn0 = (wave >> 1) * WTN;
-    const int Kb = K >> 1;                                   // packed bytes per row
-    const int KT = (Kb + kRowBytes - 1) / kRowBytes;         // stages; the last may be partial (zero-filled)
+    const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+    const int Kb = K >> 1;              // packed bytes per row
+    const int KT = Kb / kRowBytes;      // stages, all whole (host-checked)
 
-    // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
-    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..511 are W); lane l fills slot l & 3 of row l >> 2.
-    const uint8_t *xtile = Xq + (int64_t)m0 * Kb;
-    const uint8_t *wtile = Wq + (int64_t)n0 * Kb;
-    uint32_t goff[kChunksPerWave];   // byte offset of this lane's piece inside the operand tile, stage 0
-    int gcol[kChunksPerWave];        // byte column of that piece inside the 64-byte stage row
-#pragma unroll
-    for (int i = 0; i < kChunksPerWave; ++i) {
-        const int c = wave + 4 * i;
-        const int row_t = kRowsPerChunk * c + lane / kPieces;
-        const int piece = (lane % kPieces) ^ swz(row_t);
-        const bool is_x = i < kChunksPerWave / 2;            // c < 16
-        const int r = is_x ? min(row_t, M - 1 - m0) : min(row_t - BM, N - 1 - n0);   // edge rows re-read the last valid row
-        goff[i] = (uint32_t)r * (uint32_t)Kb + piece * 16;
-        gcol[i] = piece * 16;
+    // ---- dequantisation scales of the tile's rows and columns: thread t fetches x_scale[m0 + t] and
+    // w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
+    // the ring) once the loop is over.
+    float my_sx = 0.0f, my_sw = 0.0f;
+    if constexpr (!RAW) {
+        if (m0 + tid < M) my_sx = x_scale[m0 + tid];
+        if (tid < TN && n0 + tid < N) my_sw = w_scale[n0 + tid];
     }
 
+    // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
+    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..383 are W); lane l fills slot l & 3 of row l >> 2.
+    const uint8_t *xtile = Xq + (int64_t)m0 * Kb;
+    const uint8_t *wtile = Wq + (int64_t)n0 * Kb;
+    uint32_t goff[kChunks];   // byte offset of this lane's piece inside the operand tile, stage 0
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i) {
+        const int row_t = 16 * (wave + 4 * i) + lane / 4;
+        const int piece = (lane % 4) ^ swz(row_t);
+        const int r = i < kXChunks ? min(row_t, M - 1 - m0) : min(row_t - TM, N - 1 - n0);   // edge rows re-read the last valid row
+        goff[i] = (uint32_t)r * (uint32_t)Kb + piece * 16;
+    }
     // LDS-direct loads are issued from inline assembly so that the compiler does not serialise every
-    // later LDS read behind them; completion is tracked by hand with vmcnt (they retire in order).
+    // later LDS read behind them; completion is tracked by hand with vmcnt.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
     const uint32_t wave_lds = lds_base + __builtin_amdgcn_readfirstlane(wave) * 1024;
-    const int KT_full = Kb / kRowBytes;
-    // chunk i (0 .. kChunksPerWave-1) of this wavefront's share of stage kt; chunk wave + 4 i sits 4096 i further on
-    auto load_chunk_fast = [&](int kt, int i) {     // kt < KT_full: a whole stage inside K
-        const uint32_t sl = wave_lds + (kt % kStages) * kStageBytes;
-        const uint32_t koff = (uint32_t)kt * kRowBytes;
-        lds_dma16((i < kChunksPerWave / 2 ? xtile : wtile) + koff, goff[i], sl + i * 4096);
-    };
+    // chunk i of this wavefront's share of stage kt; chunk wave + 4 i sits 4096 i further on
     auto load_chunk = [&](int kt, int i) {
-        const uint32_t sl = wave_lds + (kt % kStages) * kStageBytes;
-        const uint32_t koff = (uint32_t)kt * kRowBytes;
-        if (kt < KT_full) {
-            lds_dma16((i < kChunksPerWave / 2 ? xtile : wtile) + koff, goff[i], sl + i * 4096);
-        } else if (kt < KT) {   // ragged last stage: pieces past the end of K come from a zero constant
-            const uint8_t *g = (i < kChunksPerWave / 2 ? xtile : wtile) + (goff[i] + koff);
-            if ((int)koff + gcol[i] >= Kb) g = reinterpret_cast<const uint8_t *>(&kZeroPiece);
-            lds_dma16_addr(g, sl + i * 4096);
-        } else {                // past the end: a dummy fill keeps the vmcnt bookkeeping uniform
-            lds_dma16_addr(reinterpret_cast<const uint8_t *>(&kZeroPiece), sl + i * 4096);
-        }
+        const uint32_t sl = wave_lds + ((unsigned)kt % kStages) * kStageBytes;
+        lds_dma16((i < kXChunks ? xtile : wtile) + (uint32_t)kt * kRowBytes, goff[i], sl + i * 4096);
     };
 
     // ---- LDS -> registers: fragment of 32 rows x 32 packed codes per lane-half
@@ -195,174 +125,123 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
 #pragma unroll
     for (int ks = 0; ks < kSubSteps; ++ks) foff[ks] = frow * kRowBytes + (((2 * ks + (lane >> 5)) ^ fswz) << 4);
     const int xslab = wm0 * kRowBytes;
-    const int wslab = (BM + wn0) * kRowBytes;
+    const int wslab = (TM + wn0) * kRowBytes;
 
-    uint4 px[FM], pw[FN];
-    // fragment f of K64 step ks of stage kt: f < FM is X rows 32 f .., otherwise W rows 32 (f - FM) ..
+    uint4 raw[NF];   // packed fragments of one K64 step: 0..3 X rows 32 f .., 4..5 W rows 32 (f - 4) ..
     auto read_frag = [&](int kt, int ks, auto F) {
         constexpr int f = decltype(F)::value;
-        const uint8_t *sbase = lds + (kt % kStages) * kStageBytes + foff[ks];
-        if constexpr (f < FM) px[f] = *reinterpret_cast<const uint4 *>(sbase + xslab + f * 32 * kRowBytes);
-        else pw[f - FM] = *reinterpret_cast<const uint4 *>(sbase + wslab + (f - FM) * 32 * kRowBytes);
+        const uint8_t *sbase = lds + ((unsigned)kt % kStages) * kStageBytes + foff[ks];
+        if constexpr (f < XF) raw[f] = *reinterpret_cast<const uint4 *>(sbase + xslab + f * 32 * kRowBytes);
+        else raw[f] = *reinterpret_cast<const uint4 *>(sbase + wslab + (f - XF) * 32 * kRowBytes);
     };
 
-    v16i acc[FM][FN];
+    v16i acc[XF][WF];
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < XF; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
+        for (int j = 0; j < WF; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // Widened operands are double-buffered: while the 32 MFMAs of one K64 step run, the fragments of the
-    // next step are fetched from LDS and widened in their shadow (3 VALU operations per packed dword).
-    v4i xop[2][FM][2], wop[2][FN][2];
-    // widen packed dword number d (0..31) of the pending fragments into buffer PAR:
-    // fragment d / 4 (0-3: X rows, 4-7: W rows), dword d % 4 -> operand half (d % 4) / 2, bytes 8 (d % 2)..
-    auto widen_dword = [&](auto PAR, auto D) {
-        constexpr int par = decltype(PAR)::value, d = decltype(D)::value;
-        constexpr int f = d / 4, c = d % 4, h = c / 2, e = (c % 2) * 2;
-        if constexpr (f < FM) {
-            const uint32_t p = c == 0 ? px[f].x : c == 1 ? px[f].y : c == 2 ? px[f].z : px[f].w;
-            xop[par][f][h][e] = (int)nib_lo(p);
-            xop[par][f][h][e + 1] = (int)nib_hi(p);
-        } else {
-            const uint32_t p = c == 0 ? pw[f - FM].x : c == 1 ? pw[f - FM].y : c == 2 ? pw[f - FM].z : pw[f - FM].w;
-            wop[par][f - FM][h][e] = (int)nib_lo(p);
-            wop[par][f - FM][h][e + 1] = (int)nib_hi(p);
-        }
-    };
-    auto widen_range = [&](auto PAR, auto LO, auto HI) {   // dwords LO .. HI-1
-        constexpr int lo = decltype(LO)::value, hi = decltype(HI)::value;
-        if constexpr (lo < hi) {
-            widen_dword(PAR, std::integral_constant<int, lo>{});
-            if constexpr (lo + 1 < hi) widen_dword(PAR, std::integral_constant<int, lo + 1>{});
-            static_assert(hi - lo <= 2, "at most two dwords per MFMA slot");
-        }
-    };
-    auto widen_all = [&](auto PAR) {
-#define CONVROT_W(d) widen_dword(PAR, std::integral_constant<int, d>{});
-        CONVROT_W(0) CONVROT_W(1) CONVROT_W(2) CONVROT_W(3) CONVROT_W(4) CONVROT_W(5) CONVROT_W(6) CONVROT_W(7)
-        CONVROT_W(8) CONVROT_W(9) CONVROT_W(10) CONVROT_W(11) CONVROT_W(12) CONVROT_W(13) CONVROT_W(14) CONVROT_W(15)
-        CONVROT_W(16) CONVROT_W(17) CONVROT_W(18) CONVROT_W(19) CONVROT_W(20) CONVROT_W(21) CONVROT_W(22) CONVROT_W(23)
-        CONVROT_W(24) CONVROT_W(25) CONVROT_W(26) CONVROT_W(27) CONVROT_W(28) CONVROT_W(29) CONVROT_W(30) CONVROT_W(31)
-#undef CONVROT_W
+    // A K64 step is two MFMAs per accumulator tile: half 0 on the first two dwords of every fragment,
+    // half 1 on the last two.  op[h][f] holds the widened dwords 2h, 2h+1 of fragment f.  The two halves
+    // leapfrog: while the 8 MFMAs of half 0 run, half 1 of the same step is widened and the fragment
+    // registers, now spent, are refilled from LDS with the next step; while half 1 runs, half 0 of
+    // the next step is widened into the registers half 0 has just released.
+    v4i op[2][NF];
+    auto widen_dword = [&](auto H, auto F, auto C) {   // dword 2 H + C of fragment F
+        constexpr int h = decltype(H)::value, f = decltype(F)::value, c = decltype(C)::value, d = 2 * h + c;
+        const uint32_t p = d == 0 ? raw[f].x : d == 1 ? raw[f].y : d == 2 ? raw[f].z : raw[f].w;
+        op[h][f][2 * c] = (int)nib_lo(p);
+        op[h][f][2 * c + 1] = (int)nib_hi(p);
     };
 
-    // One K64 step, slot by slot, in issue order.  A wavefront issues in order and is alone on its SIMD,
-    // so whatever stalls at issue (a burst of LDS reads or of LDS-direct loads queueing up, a barrier)
-    // idles the MFMA pipe; every memory instruction therefore gets an MFMA slot of its own.  Slot m:
-    //   MFMA m (h = m / 16, i = m / 4 % 4, j = m % 4) on operand buffer PAR
-    //   m < 8        ds_read of fragment m of the next step (stage nkt, K64 step nks)
-    //   8 <= m < 16  LDS-direct load of chunk m - 8 of stage rst (MODE kRefillFast / kRefillAny)
-    //   m >= 8       widening of the fetched fragments into buffer PAR ^ 1, 32 dwords over 24 slots
-    // Scheduling barriers pin this order.
-    constexpr int kNoSync = 0, kRefillFast = 1, kRefillAny = 2, kDrain = 3;
-    auto step_slot = [&](auto PAR, auto MI, auto MODE, int nkt, int nks, int rst) {
-        constexpr int par = decltype(PAR)::value, m = decltype(MI)::value, mode = decltype(MODE)::value;
-        constexpr int h = m / 16, i = (m / 4) % 4, j = m % 4;
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop[par][j][h], xop[par][i][h], acc[i][j], 0, 0, 0);
-        if constexpr (m < FM + FN) read_frag(nkt, nks, std::integral_constant<int, m>{});
-        if constexpr (m >= 8 && m - 8 < kChunksPerWave) {
-            if constexpr (mode == kRefillFast) load_chunk_fast(rst, m - 8);
-            if constexpr (mode == kRefillAny) load_chunk(rst, m - 8);
-        }
-        if constexpr (m >= 8) {
-            constexpr int k = m - 8;   // 0..23 -> dwords [k*32/24, (k+1)*32/24)
-            widen_range(std::integral_constant<int, par ^ 1>{}, std::integral_constant<int, k * 32 / 24>{},
-                        std::integral_constant<int, (k + 1) * 32 / 24>{});
+    // One K64 step, slot by slot, in issue order (scheduling barriers pin it).  A wavefront issues in
+    // order, so every memory instruction gets an MFMA slot of its own instead of queueing up in a burst.
+    //   half 0, slot m:  MFMA (i = m % 4, j = m / 4) on op[0];  m < 6: widen half 1 of fragment m, then
+    //                    fetch fragment m of the next step (stage nkt, K64 step nks) over it
+    //   half 1, slot m:  MFMA on op[1];  widen dwords [3m/2, 3(m+1)/2) of the 12 half-0 dwords of the next
+    //                    step;  REFILL, m < 6: LDS-direct load of chunk m of stage rkt
+    auto half0_slot = [&](auto MI, int nkt, int nks) {
+        constexpr int m = decltype(MI)::value, i = m % 4, j = m / 4;
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(op[0][XF + j], op[0][i], acc[i][j], 0, 0, 0);
+        if constexpr (m < NF) {
+            widen_dword(std::integral_constant<int, 1>{}, std::integral_constant<int, m>{}, std::integral_constant<int, 0>{});
+            widen_dword(std::integral_constant<int, 1>{}, std::integral_constant<int, m>{}, std::integral_constant<int, 1>{});
+            read_frag(nkt, nks, std::integral_constant<int, m>{});
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    // Except with kNoSync the step opens with the wait for stage nkt (this wavefront's share of it:
-    // LDS-direct loads retire in order, `behind` later stages may still be in flight) and the block
-    // barrier that extends the guarantee to everybody's share.
-    auto step = [&](auto PAR, auto MODE, int nkt, int nks, int rst, int behind) {
-        constexpr int mode = decltype(MODE)::value;
+    auto half1_slot = [&](auto MI, auto REFILL, int rkt) {
+        constexpr int m = decltype(MI)::value, i = m % 4, j = m / 4;
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(op[1][XF + j], op[1][i], acc[i][j], 0, 0, 0);
+        if constexpr (decltype(REFILL)::value && m < kChunks) load_chunk(rkt, m);
+        constexpr int lo = 3 * m / 2, hi = 3 * (m + 1) / 2;   // 12 dwords over 8 slots
+        if constexpr (lo < hi)
+            widen_dword(std::integral_constant<int, 0>{}, std::integral_constant<int, lo / 2>{}, std::integral_constant<int, lo % 2>{});
+        if constexpr (lo + 1 < hi)
+            widen_dword(std::integral_constant<int, 0>{}, std::integral_constant<int, (lo + 1) / 2>{}, std::integral_constant<int, (lo + 1) % 2>{});
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (mode != kNoSync) {
-            if constexpr (mode == kDrain) {
-                if (behind >= 1 && kStages > 3) wait_vmcnt<(kStages > 3 ? 1 : 0) * kChunksPerWave>();
-                else wait_vmcnt<0>();
-            } else {
-                wait_vmcnt<(kStages - 3) * kChunksPerWave>();
-            }
+    };
+    // With SYNC the step opens with the wait for stage nkt (all of this wavefront's loads: with a ring
+    // of three only that stage is in flight) and the block barrier that extends it to everybody's share.
+    auto step = [&](auto SYNC, auto REFILL, int nkt, int nks, int rkt) {
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(SYNC)::value) {
+            wait_vmcnt<0>();
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
         }
-#define CONVROT_SLOT(m) step_slot(PAR, std::integral_constant<int, m>{}, MODE, nkt, nks, rst);
-        CONVROT_SLOT(0) CONVROT_SLOT(1) CONVROT_SLOT(2) CONVROT_SLOT(3) CONVROT_SLOT(4) CONVROT_SLOT(5)
-        CONVROT_SLOT(6) CONVROT_SLOT(7) CONVROT_SLOT(8) CONVROT_SLOT(9) CONVROT_SLOT(10) CONVROT_SLOT(11)
-        CONVROT_SLOT(12) CONVROT_SLOT(13) CONVROT_SLOT(14) CONVROT_SLOT(15) CONVROT_SLOT(16) CONVROT_SLOT(17)
-        CONVROT_SLOT(18) CONVROT_SLOT(19) CONVROT_SLOT(20) CONVROT_SLOT(21) CONVROT_SLOT(22) CONVROT_SLOT(23)
-        CONVROT_SLOT(24) CONVROT_SLOT(25) CONVROT_SLOT(26) CONVROT_SLOT(27) CONVROT_SLOT(28) CONVROT_SLOT(29)
-        CONVROT_SLOT(30) CONVROT_SLOT(31)
-#undef CONVROT_SLOT
+#define CONVROT_H0(m) half0_slot(std::integral_constant<int, m>{}, nkt, nks);
+        CONVROT_H0(0) CONVROT_H0(1) CONVROT_H0(2) CONVROT_H0(3) CONVROT_H0(4) CONVROT_H0(5) CONVROT_H0(6) CONVROT_H0(7)
+#undef CONVROT_H0
+#define CONVROT_H1(m) half1_slot(std::integral_constant<int, m>{}, REFILL, rkt);
+        CONVROT_H1(0) CONVROT_H1(1) CONVROT_H1(2) CONVROT_H1(3) CONVROT_H1(4) CONVROT_H1(5) CONVROT_H1(6) CONVROT_H1(7)
+#undef CONVROT_H1
     };
 
-    // ---- dequantisation scales of the tile's 256 rows and 256 columns: thread t fetches x_scale[m0 + t]
-    // and w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
-    // the ring) once the loop is over.  x_scale carries the 2^-8 that undoes the 16 * 16 of the widening.
-    float my_sx = 0.0f, my_sw = 0.0f;
-    if constexpr (!RAW) {
-        if (m0 + tid < M) my_sx = x_scale[m0 + tid] * 0.00390625f;
-        if (n0 + tid < N) my_sw = w_scale[n0 + tid];
+    // ---- pipeline: stages 0 and 1 in flight; when stage 0 has landed its first fragments are fetched
+    // and their half 0 widened.  The block meets once per stage, at the start of the stage's second
+    // K64 step: stage kt+1 must have landed by then (its first fragments are fetched during that
+    // step), and the buffer stage kt-1 vacated is refilled with stage kt+2.  The last two stages
+    // refill nothing (what they fetch past the last stage is a ring buffer whose contents are unused).
+#pragma unroll
+    for (int i = 0; i < kChunks; ++i) load_chunk(0, i);
+    if (KT > 1) {
+#pragma unroll
+        for (int i = 0; i < kChunks; ++i) load_chunk(1, i);
+        wait_vmcnt<kChunks>();
+    } else {
+        wait_vmcnt<0>();
     }
-
-    // ---- pipeline: stages 0 .. S-2 are in flight before the loop (stages past the end of K are dummy
-    // fills, so that the count of loads in flight does not depend on K).  The block meets once per
-    // stage, at the start of the stage's last K64 step: stage kt+1 must have landed by then (its first
-    // fragments are fetched during that step), and the buffer stage kt-1 vacated is refilled with
-    // stage kt+S-1.
-    static_assert(kStages == 3 || kStages == 4, "wait counts below are written for 3 or 4 stages");
-    static_assert(kSubSteps % 2 == 0, "operand double-buffer parity must return to 0 every stage");
-    static_assert(kChunksPerWave <= 24 && FM + FN == 8, "slot plan of a K64 step");
-#pragma unroll
-    for (int s = 0; s < kStages - 1; ++s)
-#pragma unroll
-        for (int i = 0; i < kChunksPerWave; ++i) load_chunk(s, i);
-    wait_vmcnt<(kStages - 2) * kChunksPerWave>();
     __syncthreads();
 #define CONVROT_F(f) read_frag(0, 0, std::integral_constant<int, f>{});
-    CONVROT_F(0) CONVROT_F(1) CONVROT_F(2) CONVROT_F(3) CONVROT_F(4) CONVROT_F(5) CONVROT_F(6) CONVROT_F(7)
+    CONVROT_F(0) CONVROT_F(1) CONVROT_F(2) CONVROT_F(3) CONVROT_F(4) CONVROT_F(5)
 #undef CONVROT_F
-    widen_all(std::integral_constant<int, 0>{});
+#define CONVROT_W(f) widen_dword(std::integral_constant<int, 0>{}, std::integral_constant<int, f>{}, std::integral_constant<int, 0>{}); \
+                     widen_dword(std::integral_constant<int, 0>{}, std::integral_constant<int, f>{}, std::integral_constant<int, 1>{});
+    CONVROT_W(0) CONVROT_W(1) CONVROT_W(2) CONVROT_W(3) CONVROT_W(4) CONVROT_W(5)
+#undef CONVROT_W
 
-    // Three kinds of stage: the steady state refills a whole stage inside K (branch-free body); at
-    // most one stage refills the ragged last stage of K through the general loader; the last S-1
-    // stages refill nothing and only drain (their fetches past the last stage read a ring buffer
-    // whose contents are never used).
-    auto stage_iter = [&](int kt, auto MODE) {
-        const int last_issued = max(KT - 1, kStages - 2);
-        const int behind = min(kt + kStages - 2, last_issued) - (kt + 1);   // stages in flight behind kt+1
-#pragma unroll
-        for (int ss = 0; ss < kSubSteps; ++ss) {
-            if (ss + 1 < kSubSteps) {
-                if (ss & 1) step(std::integral_constant<int, 1>{}, std::integral_constant<int, kNoSync>{}, kt, ss + 1, 0, 0);
-                else step(std::integral_constant<int, 0>{}, std::integral_constant<int, kNoSync>{}, kt, ss + 1, 0, 0);
-            } else {
-                if (ss & 1) step(std::integral_constant<int, 1>{}, MODE, kt + 1, 0, kt + kStages - 1, behind);
-                else step(std::integral_constant<int, 0>{}, MODE, kt + 1, 0, kt + kStages - 1, behind);
-            }
-        }
-    };
-    const int KT_fast = max(0, KT_full - (kStages - 1));     // stages whose refill is a whole stage inside K
-    const int KT_refill = max(0, KT - (kStages - 1));        // stages that refill anything at all
     int kt = 0;
-    for (; kt < KT_fast; ++kt) stage_iter(kt, std::integral_constant<int, kRefillFast>{});
-    for (; kt < KT_refill; ++kt) stage_iter(kt, std::integral_constant<int, kRefillAny>{});
-    for (; kt < KT; ++kt) stage_iter(kt, std::integral_constant<int, kDrain>{});
+    for (; kt < KT - 2; ++kt) {
+        step(std::false_type{}, std::false_type{}, kt, 1, 0);
+        step(std::true_type{}, std::true_type{}, kt + 1, 0, kt + 2);
+    }
+    for (; kt < KT; ++kt) {
+        step(std::false_type{}, std::false_type{}, kt, 1, 0);
+        step(std::true_type{}, std::false_type{}, kt + 1, 0, 0);
+    }
 
-    // ---- epilogue.  Lane l, register r of a 32x32 tile: m = l % 32, n = 8 (r/4) + 4 (l/32) + r % 4.
-    wait_vmcnt<0>();         // drain the (unused) tail prefetches before their LDS buffers are reused
+    // ---- epilogue.  Lane l, register r of a 32x32 accumulator tile: m = l % 32, n = 8 (r/4) + 4 (l/32) + r % 4.
     if constexpr (RAW) {
         const bool vec_ok = (N & 3) == 0;
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
+        for (int i = 0; i < XF; ++i) {
             const int m = m0 + wm0 + i * 32 + (lane & 31);
             if (m >= M) continue;
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
+            for (int j = 0; j < WF; ++j) {
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb) {
                     const int n = n0 + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4;
@@ -382,32 +261,31 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
             }
         }
     } else {
-        float *sx_lds = reinterpret_cast<float *>(lds + kLdsBytes), *sw_lds = sx_lds + BM;
-        sx_lds[tid] = my_sx;
-        sw_lds[tid] = my_sw;
+        float *sx_lds = reinterpret_cast<float *>(lds + kRingBytes), *sw_lds = sx_lds + TM;
+        sx_lds[tid] = my_sx * 0.00390625f;   // 2^-8 undoes the 16 * 16 of the widening
+        if (tid < TN) sw_lds[tid] = my_sw;
         __syncthreads();     // every wavefront has finished reading the ring; the scales are visible
         // `interior`: the tile lies wholly inside Y and rows of Y are 16-byte multiples, so the stores need
         // no bounds checks (uniform over the block).
-        const bool interior = m0 + BM <= M && n0 + BN <= N && (N & 7) == 0;
-        // lane l, register r of a 32x32 accumulator tile: m = l % 32, n = 8 (r / 4) + 4 (l / 32) + r % 4
-        float swn[FN][4][4], sxm[FM];
+        const bool interior = m0 + TM <= M && n0 + TN <= N && (N & 7) == 0;
+        float swn[WF][4][4], sxm[XF];
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
+        for (int j = 0; j < WF; ++j)
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
                 const float4 v = *reinterpret_cast<const float4 *>(sw_lds + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4);
                 swn[j][rb][0] = v.x; swn[j][rb][1] = v.y; swn[j][rb][2] = v.z; swn[j][rb][3] = v.w;
             }
 #pragma unroll
-        for (int i = 0; i < FM; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
-        uint8_t *stage = lds + wave * (32 * kEpiPitch);     // this wavefront's 32 x 128 bf16 staging tile
-        const int ncol = n0 + wn0 + (lane & 15) * 8;         // first of this lane's 8 output columns
+        for (int i = 0; i < XF; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
+        uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x 64 bf16 staging tile
+        const int ncol = n0 + wn0 + (lane & 7) * 8;              // first of this lane's 8 output columns
         auto body = [&](auto INTERIOR) {
 #pragma unroll
-            for (int i = 0; i < FM; ++i) {
+            for (int i = 0; i < XF; ++i) {
                 const int mrow = m0 + wm0 + i * 32;
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
+                for (int j = 0; j < WF; ++j)
 #pragma unroll
                     for (int rb = 0; rb < 4; ++rb) {
                         float y[4];
@@ -417,11 +295,11 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_kernel(
                         *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
                             make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
                     }
-                // same wavefront reads back row-contiguous: 16 lanes cover one 256-byte row, 4 rows per pass
+                // the same wavefront reads back row-contiguous: 8 lanes cover one 128-byte row, 8 rows per pass
 #pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const int r = it * 4 + (lane >> 4);
-                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + (lane & 15) * 16);
+                for (int it = 0; it < 4; ++it) {
+                    const int r = it * 8 + (lane >> 3);
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + (lane & 7) * 16);
                     const int mo = mrow + r;
                     uint16_t *dst = Y + (int64_t)mo * N + ncol;
                     if constexpr (decltype(INTERIOR)::value) {
@@ -451,7 +329,7 @@ template <bool RAW>
 hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, int M, int N, int K,
                       void *Y, int32_t *acc, hipStream_t stream)
 {
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
     const int ntiles = tiles_m * tiles_n;
     const int grid = ((ntiles + kNumXcd - 1) / kNumXcd) * kNumXcd;
     static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
@@ -473,6 +351,8 @@ hipError_t launch_gemm_w4a4(const void *Xq, const float *x_scale, const void *Wq
                             hipStream_t stream)
 {
     if (M == 0 || N == 0) return hipSuccess;
+    if (K % (2 * kRowBytes) != 0)   // a ragged last stage: the general kernel zero-fills it
+        return launch_gemm_w4a4_generic(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, Y_bf16, acc_i32, stream);
     if (acc_i32)
         return launch_one<true>(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, nullptr, acc_i32, stream);
     return launch_one<false>(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, Y_bf16, nullptr, stream);

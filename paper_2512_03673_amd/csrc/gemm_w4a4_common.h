@@ -1,0 +1,101 @@
+// Shared pieces of the two W4A4 GEMM kernels of libconvrot (tile shape, LDS swizzle, LDS-direct
+// loads, tile order).  See gemm_w4a4.hip for the description of the method.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+namespace convrot {
+namespace gemm {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+
+constexpr int BM = 256, BN = 256;        // block tile
+constexpr int kThreads = 256;            // 4 wavefronts, 2 x 2
+constexpr int WTM = 128, WTN = 128;      // wavefront tile
+constexpr int FM = WTM / 32, FN = WTN / 32;
+constexpr int kRowBytes = 64;                             // packed bytes of K per row per stage (64 B = 128 codes)
+constexpr int kStages = 4;
+constexpr int kPieces = kRowBytes / 16;                   // 16-byte pieces per LDS row
+constexpr int kSubSteps = kRowBytes / 32;                 // K64 steps (one ds_read_b128 per fragment) per stage
+constexpr int kStageBytes = (BM + BN) * kRowBytes;
+constexpr int kRingBytes = kStages * kStageBytes;         // 128 KB
+constexpr int kChunksPerWave = kStageBytes / 1024 / 4;    // 1 KB LDS-direct loads per wavefront per stage
+constexpr int kRowsPerChunk = 1024 / kRowBytes;
+constexpr int kNumXcd = 8;
+
+static_assert(kChunksPerWave * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
+static_assert(kSubSteps % 2 == 0, "operand double-buffer parity must return to 0 every stage");
+static_assert(kChunksPerWave <= 24 && FM + FN == 8, "slot plan of a K64 step");
+
+__device__ __forceinline__ uint32_t nib_lo(uint32_t p) { return (p << 4) & 0xF0F0F0F0u; }
+__device__ __forceinline__ uint32_t nib_hi(uint32_t p) { return p & 0xF0F0F0F0u; }
+
+// Which of the four 16-byte slots of its LDS row a piece lands in: slot = piece ^ swz(row).
+// For any 8 consecutive rows the (row & 1, slot) pairs are distinct (32 banks), and for any 16
+// consecutive rows the (row & 3, slot) pairs are distinct (64 banks).
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    // gfx9 encoding: vmcnt = {imm[15:14], imm[3:0]}, expcnt = imm[6:4], lgkmcnt = imm[11:8]
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+// global_load_lds_dwordx4: lane l copies 16 bytes from its global address to LDS address M0 + 16 l.
+__device__ __forceinline__ void lds_dma16(const uint8_t *base, uint32_t lane_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void lds_dma16_addr(const uint8_t *lane_ptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(lane_ptr), "s"(lds_addr) : "memory");
+}
+// global_load_lds_dword: lane l copies 4 bytes from its global address to LDS address M0 + 4 l.
+__device__ __forceinline__ void lds_dma4_addr(const void *lane_ptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :: "v"(lane_ptr), "s"(lds_addr) : "memory");
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    v2bf r = __builtin_convertvector((v2f){a, b}, v2bf);   // v_cvt_pk_bf16_f32: round to nearest even
+    return *reinterpret_cast<uint32_t *>(&r);
+}
+
+// Tile order: blocks are dealt round-robin to the 8 XCDs by the hardware, each XCD has its own
+// L2.  Give every XCD one contiguous range of logical tile ids, and walk that range in bands of
+// `GM` tile rows so that tiles that run together share X and W panels.  `bid` may run past the
+// grid (a persistent block asks for bid + gridDim.x, ...): false when XCD bid % 8 has no such tile.
+__device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int ntiles = tiles_m * tiles_n;
+    const int per_xcd = (ntiles + kNumXcd - 1) / kNumXcd;
+    if (bid / kNumXcd >= per_xcd) return false;
+    const int id = (bid % kNumXcd) * per_xcd + bid / kNumXcd;
+    if (id >= ntiles) return false;
+    constexpr int GM = 6;
+    const int band = id / (GM * tiles_n);
+    const int first_m = band * GM;
+    const int rows_in_band = min(GM, tiles_m - first_m);
+    const int local = id - band * GM * tiles_n;
+    tm = first_m + local % rows_in_band;
+    tn = local / rows_in_band;
+    return true;
+}
+
+}  // namespace gemm
+
+// One output tile per block, any K the library accepts (gemm_w4a4_generic.hip).
+hipError_t launch_gemm_w4a4_generic(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
+                                    int M, int N, int K, void *Y_bf16, int32_t *acc_i32, hipStream_t stream);
+
+}  // namespace convrot

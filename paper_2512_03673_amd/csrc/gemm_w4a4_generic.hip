@@ -1,0 +1,370 @@
+// Kernel B of libconvrot, general form: one 256 x 256 output tile per block, any K the library
+// accepts (K % 32 == 0; a ragged last stage of the ring is zero-filled).  Same arithmetic, LDS layout
+// and K64-step schedule as the persistent kernel in gemm_w4a4.hip, which takes the shapes with
+// K % 128 == 0 and K >= 384; here the ring is primed and drained per tile and the epilogue stages
+// its output in the ring.
+#include "gemm_w4a4_common.h"
+
+namespace convrot {
+
+using namespace gemm;
+
+namespace {
+
+constexpr int kLdsBytes = kRingBytes;
+constexpr int kLdsTotal = kLdsBytes + (BM + BN) * 4;      // + the tile's dequantisation scales
+constexpr int kEpiPitch = WTN * 2 + 16;                   // bf16 row of the wavefront tile + pad
+static_assert(4 * 32 * kEpiPitch <= kLdsBytes, "epilogue staging must fit the ring");
+static_assert(kLdsTotal <= 160 * 1024, "LDS");
+
+// 16 zero bytes for LDS-direct loads that fall past the end of K.
+__device__ const uint4 kZeroPiece = {0u, 0u, 0u, 0u};
+
+}  // namespace
+
+template <bool RAW>
+__global__ __launch_bounds__(kThreads) void gemm_w4a4_generic_kernel(
+    const uint8_t *__restrict__ Xq, const float *__restrict__ x_scale, const uint8_t *__restrict__ Wq,
+    const float *__restrict__ w_scale, int M, int N, int K, uint16_t *__restrict__ Y,
+    int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+
+    int tm, tn;
+    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave & 1) * WTM, wn0 = (wave >> 1) * WTN;
+    const int Kb = K >> 1;                                   // packed bytes per row
+    const int KT = (Kb + kRowBytes - 1) / kRowBytes;         // stages; the last may be partial (zero-filled)
+
+    // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
+    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..511 are W); lane l fills slot l & 3 of row l >> 2.
+    const uint8_t *xtile = Xq + (int64_t)m0 * Kb;
+    const uint8_t *wtile = Wq + (int64_t)n0 * Kb;
+    uint32_t goff[kChunksPerWave];   // byte offset of this lane's piece inside the operand tile, stage 0
+    int gcol[kChunksPerWave];        // byte column of that piece inside the 64-byte stage row
+#pragma unroll
+    for (int i = 0; i < kChunksPerWave; ++i) {
+        const int c = wave + 4 * i;
+        const int row_t = kRowsPerChunk * c + lane / kPieces;
+        const int piece = (lane % kPieces) ^ swz(row_t);
+        const bool is_x = i < kChunksPerWave / 2;            // c < 16
+        const int r = is_x ? min(row_t, M - 1 - m0) : min(row_t - BM, N - 1 - n0);   // edge rows re-read the last valid row
+        goff[i] = (uint32_t)r * (uint32_t)Kb + piece * 16;
+        gcol[i] = piece * 16;
+    }
+
+    // LDS-direct loads are issued from inline assembly so that the compiler does not serialise every
+    // later LDS read behind them; completion is tracked by hand with vmcnt (they retire in order).
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
+    const uint32_t wave_lds = lds_base + __builtin_amdgcn_readfirstlane(wave) * 1024;
+    const int KT_full = Kb / kRowBytes;
+    // chunk i (0 .. kChunksPerWave-1) of this wavefront's share of stage kt; chunk wave + 4 i sits 4096 i further on
+    auto load_chunk_fast = [&](int kt, int i) {     // kt < KT_full: a whole stage inside K
+        const uint32_t sl = wave_lds + (kt % kStages) * kStageBytes;
+        const uint32_t koff = (uint32_t)kt * kRowBytes;
+        lds_dma16((i < kChunksPerWave / 2 ? xtile : wtile) + koff, goff[i], sl + i * 4096);
+    };
+    auto load_chunk = [&](int kt, int i) {
+        const uint32_t sl = wave_lds + (kt % kStages) * kStageBytes;
+        const uint32_t koff = (uint32_t)kt * kRowBytes;
+        if (kt < KT_full) {
+            lds_dma16((i < kChunksPerWave / 2 ? xtile : wtile) + koff, goff[i], sl + i * 4096);
+        } else if (kt < KT) {   // ragged last stage: pieces past the end of K come from a zero constant
+            const uint8_t *g = (i < kChunksPerWave / 2 ? xtile : wtile) + (goff[i] + koff);
+            if ((int)koff + gcol[i] >= Kb) g = reinterpret_cast<const uint8_t *>(&kZeroPiece);
+            lds_dma16_addr(g, sl + i * 4096);
+        } else {                // past the end: a dummy fill keeps the vmcnt bookkeeping uniform
+            lds_dma16_addr(reinterpret_cast<const uint8_t *>(&kZeroPiece), sl + i * 4096);
+        }
+    };
+
+    // ---- LDS -> registers: fragment of 32 rows x 32 packed codes per lane-half
+    const int frow = lane & 31;
+    const int fswz = swz(frow);                              // tile rows differ from frow by multiples of 32
+    int foff[kSubSteps];                                     // per K64 step: byte offset inside a 32-row slab
+#pragma unroll
+    for (int ks = 0; ks < kSubSteps; ++ks) foff[ks] = frow * kRowBytes + (((2 * ks + (lane >> 5)) ^ fswz) << 4);
+    const int xslab = wm0 * kRowBytes;
+    const int wslab = (BM + wn0) * kRowBytes;
+
+    uint4 px[FM], pw[FN];
+    // fragment f of K64 step ks of stage kt: f < FM is X rows 32 f .., otherwise W rows 32 (f - FM) ..
+    auto read_frag = [&](int kt, int ks, auto F) {
+        constexpr int f = decltype(F)::value;
+        const uint8_t *sbase = lds + (kt % kStages) * kStageBytes + foff[ks];
+        if constexpr (f < FM) px[f] = *reinterpret_cast<const uint4 *>(sbase + xslab + f * 32 * kRowBytes);
+        else pw[f - FM] = *reinterpret_cast<const uint4 *>(sbase + wslab + (f - FM) * 32 * kRowBytes);
+    };
+
+    v16i acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // Widened operands are double-buffered: while the 32 MFMAs of one K64 step run, the fragments of the
+    // next step are fetched from LDS and widened in their shadow (3 VALU operations per packed dword).
+    v4i xop[2][FM][2], wop[2][FN][2];
+    // widen packed dword number d (0..31) of the pending fragments into buffer PAR:
+    // fragment d / 4 (0-3: X rows, 4-7: W rows), dword d % 4 -> operand half (d % 4) / 2, bytes 8 (d % 2)..
+    auto widen_dword = [&](auto PAR, auto D) {
+        constexpr int par = decltype(PAR)::value, d = decltype(D)::value;
+        constexpr int f = d / 4, c = d % 4, h = c / 2, e = (c % 2) * 2;
+        if constexpr (f < FM) {
+            const uint32_t p = c == 0 ? px[f].x : c == 1 ? px[f].y : c == 2 ? px[f].z : px[f].w;
+            xop[par][f][h][e] = (int)nib_lo(p);
+            xop[par][f][h][e + 1] = (int)nib_hi(p);
+        } else {
+            const uint32_t p = c == 0 ? pw[f - FM].x : c == 1 ? pw[f - FM].y : c == 2 ? pw[f - FM].z : pw[f - FM].w;
+            wop[par][f - FM][h][e] = (int)nib_lo(p);
+            wop[par][f - FM][h][e + 1] = (int)nib_hi(p);
+        }
+    };
+    auto widen_range = [&](auto PAR, auto LO, auto HI) {   // dwords LO .. HI-1
+        constexpr int lo = decltype(LO)::value, hi = decltype(HI)::value;
+        if constexpr (lo < hi) {
+            widen_dword(PAR, std::integral_constant<int, lo>{});
+            if constexpr (lo + 1 < hi) widen_dword(PAR, std::integral_constant<int, lo + 1>{});
+            static_assert(hi - lo <= 2, "at most two dwords per MFMA slot");
+        }
+    };
+    auto widen_all = [&](auto PAR) {
+#define CONVROT_W(d) widen_dword(PAR, std::integral_constant<int, d>{});
+        CONVROT_W(0) CONVROT_W(1) CONVROT_W(2) CONVROT_W(3) CONVROT_W(4) CONVROT_W(5) CONVROT_W(6) CONVROT_W(7)
+        CONVROT_W(8) CONVROT_W(9) CONVROT_W(10) CONVROT_W(11) CONVROT_W(12) CONVROT_W(13) CONVROT_W(14) CONVROT_W(15)
+        CONVROT_W(16) CONVROT_W(17) CONVROT_W(18) CONVROT_W(19) CONVROT_W(20) CONVROT_W(21) CONVROT_W(22) CONVROT_W(23)
+        CONVROT_W(24) CONVROT_W(25) CONVROT_W(26) CONVROT_W(27) CONVROT_W(28) CONVROT_W(29) CONVROT_W(30) CONVROT_W(31)
+#undef CONVROT_W
+    };
+
+    // One K64 step, slot by slot, in issue order.  A wavefront issues in order and is alone on its SIMD,
+    // so whatever stalls at issue (a burst of LDS reads or of LDS-direct loads queueing up, a barrier)
+    // idles the MFMA pipe; every memory instruction therefore gets an MFMA slot of its own.  Slot m:
+    //   MFMA m (h = m / 16, i = m / 4 % 4, j = m % 4) on operand buffer PAR
+    //   m < 8        ds_read of fragment m of the next step (stage nkt, K64 step nks)
+    //   8 <= m < 16  LDS-direct load of chunk m - 8 of stage rst (MODE kRefillFast / kRefillAny)
+    //   m >= 8       widening of the fetched fragments into buffer PAR ^ 1, 32 dwords over 24 slots
+    // Scheduling barriers pin this order.
+    constexpr int kNoSync = 0, kRefillFast = 1, kRefillAny = 2, kDrain = 3;
+    auto step_slot = [&](auto PAR, auto MI, auto MODE, int nkt, int nks, int rst) {
+        constexpr int par = decltype(PAR)::value, m = decltype(MI)::value, mode = decltype(MODE)::value;
+        constexpr int h = m / 16, i = (m / 4) % 4, j = m % 4;
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop[par][j][h], xop[par][i][h], acc[i][j], 0, 0, 0);
+        if constexpr (m < FM + FN) read_frag(nkt, nks, std::integral_constant<int, m>{});
+        if constexpr (m >= 8 && m - 8 < kChunksPerWave) {
+            if constexpr (mode == kRefillFast) load_chunk_fast(rst, m - 8);
+            if constexpr (mode == kRefillAny) load_chunk(rst, m - 8);
+        }
+        if constexpr (m >= 8) {
+            constexpr int k = m - 8;   // 0..23 -> dwords [k*32/24, (k+1)*32/24)
+            widen_range(std::integral_constant<int, par ^ 1>{}, std::integral_constant<int, k * 32 / 24>{},
+                        std::integral_constant<int, (k + 1) * 32 / 24>{});
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Except with kNoSync the step opens with the wait for stage nkt (this wavefront's share of it:
+    // LDS-direct loads retire in order, `behind` later stages may still be in flight) and the block
+    // barrier that extends the guarantee to everybody's share.
+    auto step = [&](auto PAR, auto MODE, int nkt, int nks, int rst, int behind) {
+        constexpr int mode = decltype(MODE)::value;
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (mode != kNoSync) {
+            if constexpr (mode == kDrain) {
+                if (behind >= 1 && kStages > 3) wait_vmcnt<(kStages > 3 ? 1 : 0) * kChunksPerWave>();
+                else wait_vmcnt<0>();
+            } else {
+                wait_vmcnt<(kStages - 3) * kChunksPerWave>();
+            }
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#define CONVROT_SLOT(m) step_slot(PAR, std::integral_constant<int, m>{}, MODE, nkt, nks, rst);
+        CONVROT_SLOT(0) CONVROT_SLOT(1) CONVROT_SLOT(2) CONVROT_SLOT(3) CONVROT_SLOT(4) CONVROT_SLOT(5)
+        CONVROT_SLOT(6) CONVROT_SLOT(7) CONVROT_SLOT(8) CONVROT_SLOT(9) CONVROT_SLOT(10) CONVROT_SLOT(11)
+        CONVROT_SLOT(12) CONVROT_SLOT(13) CONVROT_SLOT(14) CONVROT_SLOT(15) CONVROT_SLOT(16) CONVROT_SLOT(17)
+        CONVROT_SLOT(18) CONVROT_SLOT(19) CONVROT_SLOT(20) CONVROT_SLOT(21) CONVROT_SLOT(22) CONVROT_SLOT(23)
+        CONVROT_SLOT(24) CONVROT_SLOT(25) CONVROT_SLOT(26) CONVROT_SLOT(27) CONVROT_SLOT(28) CONVROT_SLOT(29)
+        CONVROT_SLOT(30) CONVROT_SLOT(31)
+#undef CONVROT_SLOT
+    };
+
+    // ---- dequantisation scales of the tile's 256 rows and 256 columns: thread t fetches x_scale[m0 + t]
+    // and w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
+    // the ring) once the loop is over.
+    float my_sx = 0.0f, my_sw = 0.0f;
+    if constexpr (!RAW) {
+        if (m0 + tid < M) my_sx = x_scale[m0 + tid];
+        if (n0 + tid < N) my_sw = w_scale[n0 + tid];
+    }
+
+    // ---- pipeline: stages 0 .. S-2 are in flight before the loop (stages past the end of K are dummy
+    // fills, so that the count of loads in flight does not depend on K).  The block meets once per
+    // stage, at the start of the stage's last K64 step: stage kt+1 must have landed by then (its first
+    // fragments are fetched during that step), and the buffer stage kt-1 vacated is refilled with
+    // stage kt+S-1.
+    static_assert(kStages == 3 || kStages == 4, "wait counts below are written for 3 or 4 stages");
+    static_assert(kSubSteps % 2 == 0, "operand double-buffer parity must return to 0 every stage");
+    static_assert(kChunksPerWave <= 24 && FM + FN == 8, "slot plan of a K64 step");
+#pragma unroll
+    for (int s = 0; s < kStages - 1; ++s)
+#pragma unroll
+        for (int i = 0; i < kChunksPerWave; ++i) load_chunk(s, i);
+    wait_vmcnt<(kStages - 2) * kChunksPerWave>();
+    __syncthreads();
+#define CONVROT_F(f) read_frag(0, 0, std::integral_constant<int, f>{});
+    CONVROT_F(0) CONVROT_F(1) CONVROT_F(2) CONVROT_F(3) CONVROT_F(4) CONVROT_F(5) CONVROT_F(6) CONVROT_F(7)
+#undef CONVROT_F
+    widen_all(std::integral_constant<int, 0>{});
+
+    // Three kinds of stage: the steady state refills a whole stage inside K (branch-free body); at
+    // most one stage refills the ragged last stage of K through the general loader; the last S-1
+    // stages refill nothing and only drain (their fetches past the last stage read a ring buffer
+    // whose contents are never used).
+    auto stage_iter = [&](int kt, auto MODE) {
+        const int last_issued = max(KT - 1, kStages - 2);
+        const int behind = min(kt + kStages - 2, last_issued) - (kt + 1);   // stages in flight behind kt+1
+#pragma unroll
+        for (int ss = 0; ss < kSubSteps; ++ss) {
+            if (ss + 1 < kSubSteps) {
+                if (ss & 1) step(std::integral_constant<int, 1>{}, std::integral_constant<int, kNoSync>{}, kt, ss + 1, 0, 0);
+                else step(std::integral_constant<int, 0>{}, std::integral_constant<int, kNoSync>{}, kt, ss + 1, 0, 0);
+            } else {
+                if (ss & 1) step(std::integral_constant<int, 1>{}, MODE, kt + 1, 0, kt + kStages - 1, behind);
+                else step(std::integral_constant<int, 0>{}, MODE, kt + 1, 0, kt + kStages - 1, behind);
+            }
+        }
+    };
+    const int KT_fast = max(0, KT_full - (kStages - 1));     // stages whose refill is a whole stage inside K
+    const int KT_refill = max(0, KT - (kStages - 1));        // stages that refill anything at all
+    int kt = 0;
+    for (; kt < KT_fast; ++kt) stage_iter(kt, std::integral_constant<int, kRefillFast>{});
+    for (; kt < KT_refill; ++kt) stage_iter(kt, std::integral_constant<int, kRefillAny>{});
+    for (; kt < KT; ++kt) stage_iter(kt, std::integral_constant<int, kDrain>{});
+
+    // ---- epilogue.  Lane l, register r of a 32x32 tile: m = l % 32, n = 8 (r/4) + 4 (l/32) + r % 4.
+    wait_vmcnt<0>();         // drain the (unused) tail prefetches before their LDS buffers are reused
+    if constexpr (RAW) {
+        const bool vec_ok = (N & 3) == 0;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = m0 + wm0 + i * 32 + (lane & 31);
+            if (m >= M) continue;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const int n = n0 + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4;
+                    if (n >= N) continue;
+                    int32_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = acc[i][j][rb * 4 + e] >> 8;
+                    int32_t *dst = acc_out + (int64_t)m * N + n;
+                    if (vec_ok) {
+                        *reinterpret_cast<int4 *>(dst) = make_int4(o[0], o[1], o[2], o[3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < N) dst[e] = o[e];
+                    }
+                }
+            }
+        }
+    } else {
+        float *sx_lds = reinterpret_cast<float *>(lds + kLdsBytes), *sw_lds = sx_lds + BM;
+        sx_lds[tid] = my_sx * 0.00390625f;   // 2^-8 undoes the 16 * 16 of the widening
+        sw_lds[tid] = my_sw;
+        __syncthreads();     // every wavefront has finished reading the ring; the scales are visible
+        // `interior`: the tile lies wholly inside Y and rows of Y are 16-byte multiples, so the stores need
+        // no bounds checks (uniform over the block).
+        const bool interior = m0 + BM <= M && n0 + BN <= N && (N & 7) == 0;
+        // lane l, register r of a 32x32 accumulator tile: m = l % 32, n = 8 (r / 4) + 4 (l / 32) + r % 4
+        float swn[FN][4][4], sxm[FM];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const float4 v = *reinterpret_cast<const float4 *>(sw_lds + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4);
+                swn[j][rb][0] = v.x; swn[j][rb][1] = v.y; swn[j][rb][2] = v.z; swn[j][rb][3] = v.w;
+            }
+#pragma unroll
+        for (int i = 0; i < FM; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
+        uint8_t *stage = lds + wave * (32 * kEpiPitch);     // this wavefront's 32 x 128 bf16 staging tile
+        const int ncol = n0 + wn0 + (lane & 15) * 8;         // first of this lane's 8 output columns
+        auto body = [&](auto INTERIOR) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                const int mrow = m0 + wm0 + i * 32;
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb) {
+                        float y[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) y[e] = ((float)acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
+                        const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
+                        *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
+                            make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+                    }
+                // same wavefront reads back row-contiguous: 16 lanes cover one 256-byte row, 4 rows per pass
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    const int r = it * 4 + (lane >> 4);
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + (lane & 15) * 16);
+                    const int mo = mrow + r;
+                    uint16_t *dst = Y + (int64_t)mo * N + ncol;
+                    if constexpr (decltype(INTERIOR)::value) {
+                        *reinterpret_cast<uint4 *>(dst) = v;
+                    } else {
+                        if (mo >= M || ncol >= N) continue;
+                        if ((N & 7) == 0) {
+                            *reinterpret_cast<uint4 *>(dst) = v;
+                        } else {
+                            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (ncol + e < N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                        }
+                    }
+                }
+            }
+        };
+        if (interior) body(std::true_type{});
+        else body(std::false_type{});
+    }
+}
+
+namespace {
+
+template <bool RAW>
+hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, int M, int N, int K,
+                      void *Y, int32_t *acc, hipStream_t stream)
+{
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int ntiles = tiles_m * tiles_n;
+    const int grid = ((ntiles + kNumXcd - 1) / kNumXcd) * kNumXcd;
+    static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4a4_generic_kernel<RAW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((gemm_w4a4_generic_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsTotal, stream, (const uint8_t *)Xq,
+                       x_scale, (const uint8_t *)Wq, w_scale, M, N, K, (uint16_t *)Y, acc, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemm_w4a4_generic(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
+                                    int M, int N, int K, void *Y_bf16, int32_t *acc_i32, hipStream_t stream)
+{
+    if (acc_i32) return launch_one<true>(Xq, x_scale, Wq, w_scale, M, N, K, nullptr, acc_i32, stream);
+    return launch_one<false>(Xq, x_scale, Wq, w_scale, M, N, K, Y_bf16, nullptr, stream);
+}
+
+}  // namespace convrot
