@@ -76,13 +76,50 @@ def cpu_baseline(spec, x_bits, w_bits, budget_s: float = 15.0):
             "ms_per_step": dt / rows * spec.M * 1e3}
 
 
+def measure_layer(spec, cr, wl, torch, np, steps: int, warmup: int):
+    """Kernel A, kernel B, the fused forward and the offline weight preparation of one layer (ms, rates)."""
+    stream = torch.cuda.current_stream()
+    M, K, N, g = spec.M, spec.K, spec.N, spec.group
+    x_bits, w_bits = wl.make_layer(spec)
+    X = torch.from_numpy(x_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    W = torch.from_numpy(w_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    Wq, Ws = cr.convrot_prepare_weight(W, g)
+    Xq, Xs = cr.convrot_rotquant_act(X, g)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty((cr.workspace_bytes(M, K),), dtype=torch.uint8, device="cuda")
+    fns = {"forward": lambda: cr.convlinear4bit_forward(X, Wq, Ws, g, Y, ws),
+           "gemm": lambda: cr.convrot_w4a4_gemm_dequant(Xq, Xs, Wq, Ws, Y),
+           "rotquant": lambda: cr.convrot_rotquant_act(X, g, Xq, Xs),
+           "prepare_weight": lambda: cr.convrot_prepare_weight(W, g, Wq, Ws)}
+    for _ in range(warmup):
+        fns["forward"]()
+    ms = {}
+    for name, fn in fns.items():
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        ms[name] = time_region(fn, steps, torch, stream)
+    torch.cuda.synchronize()
+    ops, bytes_a, bytes_w = 2.0 * M * K * N, 2.5 * M * K + 4.0 * M, 2.5 * N * K + 4.0 * N
+    return {"layer": spec.name, "M": M, "K": K, "N": N, "group": g,
+            "forward_ms": ms["forward"], "forward_TOPS": ops / ms["forward"] / 1e9,
+            "gemm_ms": ms["gemm"], "gemm_TOPS": ops / ms["gemm"] / 1e9,
+            "gemm_frac_i8_mfma_peak": ops / ms["gemm"] / 1e9 / I8_MFMA_PEAK_TOPS,
+            "rotquant_ms_warm": ms["rotquant"], "rotquant_GB/s_warm": bytes_a / ms["rotquant"] / 1e6,
+            "rotquant_frac_hbm_peak_warm": bytes_a / ms["rotquant"] / 1e6 / HBM_PEAK_GBS,
+            "prepare_weight_ms": ms["prepare_weight"], "prepare_weight_GB/s": bytes_w / ms["prepare_weight"] / 1e6}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    # the clocks of an idle MI355X take some 30 ms of load to settle: the default warm-up covers that
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time every layer of the five benchmark configurations (adds a 'configs' list)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards over tokens without any "
@@ -134,8 +171,8 @@ def main() -> int:
     for _ in range(max(5, args.warmup // 4)):
         kern_a(); kern_b()
     torch.cuda.synchronize()
-    ms_a = time_region(kern_a, args.steps, torch, stream)
     ms_b = time_region(kern_b, args.steps, torch, stream)
+    ms_a = time_region(kern_a, args.steps, torch, stream)
     torch.cuda.synchronize()
 
     # kernel A again with nothing of its working set left in the 256 MB Infinity Cache: a ring of
@@ -193,6 +230,10 @@ def main() -> int:
                      "unit": "TOP/s", "frac": tops_b / I8_MFMA_PEAK_TOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES["gemm_w4a4_kernel"]},
     }
+    if args.all_configs:
+        del X, Wq, Ws, Y, ws, Xq, Xs
+        out["configs"] = [dict(config=name, **measure_layer(sp, cr, wl, torch, np, min(args.steps, 100), min(args.warmup, 100)))
+                          for name, layers in wl.CONFIGS.items() for sp in layers]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(spec, x_bits, w_bits)
     print(json.dumps(out))
