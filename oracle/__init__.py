@@ -48,9 +48,9 @@ def _load():
             lib.oracle_pack4.argtypes = [vp, i64, i64, vp]
             lib.oracle_unpack4.argtypes = [vp, i64, i64, vp]
             lib.oracle_int_gemm.argtypes = [vp, vp, i64, i64, i64, vp]
-            lib.oracle_dequant.argtypes = [vp, vp, vp, i64, i64, vp]
+            lib.oracle_dequant.argtypes = [vp, vp, vp, vp, i64, i64, vp]
             lib.oracle_rotquant.argtypes = [vp, i64, i64, i32, i32, vp, vp]
-            lib.oracle_convlinear4bit.argtypes = [vp, vp, i64, i64, i64, i32, vp]
+            lib.oracle_convlinear.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
             lib.oracle_double_to_bf16.argtypes = [ctypes.c_double]
             lib.oracle_double_to_bf16.restype = ctypes.c_uint16
             _lib = lib
@@ -132,14 +132,17 @@ def int_gemm(qx: np.ndarray, qw: np.ndarray) -> np.ndarray:
     return acc
 
 
-def dequant(acc: np.ndarray, sx: np.ndarray, sw: np.ndarray) -> np.ndarray:
-    """Y = bf16(acc * sx[:, None] * sw[None, :]) as uint16 bits."""
+def dequant(acc: np.ndarray, sx: np.ndarray, sw: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """Y = bf16(acc * sx[:, None] * sw[None, :] + bias[None, :]) as uint16 bits (bias: bf16 bits [N] or None)."""
     acc = _c(acc, np.int32)
     sx = _c(sx, np.float32)
     sw = _c(sw, np.float32)
     M, N = acc.shape
+    b = None if bias is None else _c(bias, np.uint16)
+    if b is not None and b.shape != (N,):
+        raise ValueError("bias shape")
     y = np.empty((M, N), dtype=np.uint16)
-    _check(_load().oracle_dequant(_p(acc), _p(sx), _p(sw), M, N, _p(y)), "dequant")
+    _check(_load().oracle_dequant(_p(acc), _p(sx), _p(sw), _p(b), M, N, _p(y)), "dequant")
     return y
 
 
@@ -153,17 +156,26 @@ def rotquant(x_bf16: np.ndarray, g: int, qmax: int = 7) -> Tuple[np.ndarray, np.
     return codes, scale
 
 
-def convlinear4bit(x_bf16: np.ndarray, w_bf16: np.ndarray, g: int) -> np.ndarray:
-    """Whole forward: bf16 X [M,K], bf16 W [N,K] -> bf16 Y [M,N] (uint16 bits)."""
+def convlinear(x_bf16: np.ndarray, w_bf16: np.ndarray, g: int, bias: Optional[np.ndarray] = None,
+               qmax: int = 7) -> np.ndarray:
+    """Whole forward: bf16 X [M,K], bf16 W [N,K] (+ bf16 bias [N]) -> bf16 Y [M,N] (uint16 bits).
+
+    qmax = 7 is ConvLinear4bit (W4A4), qmax = 127 the W8A8 variant."""
     x = _c(x_bf16, np.uint16)
     w = _c(w_bf16, np.uint16)
     M, K = x.shape
     N, K2 = w.shape
     if K != K2:
         raise ValueError("K mismatch")
+    b = None if bias is None else _c(bias, np.uint16)
     y = np.empty((M, N), dtype=np.uint16)
-    _check(_load().oracle_convlinear4bit(_p(x), _p(w), M, N, K, int(g), _p(y)), "convlinear4bit")
+    _check(_load().oracle_convlinear(_p(x), _p(w), _p(b), M, N, K, int(g), int(qmax), _p(y)), "convlinear")
     return y
+
+
+def convlinear4bit(x_bf16: np.ndarray, w_bf16: np.ndarray, g: int, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """ConvLinear4bit forward (W4A4)."""
+    return convlinear(x_bf16, w_bf16, g, bias=bias, qmax=7)
 
 
 def double_to_bf16(v: float) -> int:

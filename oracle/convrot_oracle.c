@@ -236,14 +236,23 @@ static uint16_t double_to_bf16_rne(double v)
 
 uint16_t oracle_double_to_bf16(double v) { return double_to_bf16_rne(v); }
 
-/* Sec. 4.3 / supplement Sec. B: Y[m,n] = bf16( acc[m,n] * s_x[m] * s_w[n] ), product in double. */
-int oracle_dequant(const int32_t *acc, const float *sx, const float *sw, int64_t M, int64_t N, uint16_t *y)
+/*
+ * Sec. 4.3 / supplement Sec. B: Y[m,n] = bf16( acc[m,n] * s_x[m] * s_w[n] + b[n] ), all in double, one
+ * rounding.  The bias b (bf16 [N], may be NULL = none) is not in the paper's Eq. 10; the linear layers
+ * the paper replaces carry one, and it is taken as added to the dequantised product before the
+ * single rounding to the output type.
+ */
+int oracle_dequant(const int32_t *acc, const float *sx, const float *sw, const uint16_t *bias, int64_t M, int64_t N,
+                   uint16_t *y)
 {
     if (!acc || !sx || !sw || !y || M < 0 || N < 0) return ORACLE_ERR_ARG;
 #pragma omp parallel for schedule(static)
     for (int64_t m = 0; m < M; ++m)
-        for (int64_t n = 0; n < N; ++n)
-            y[m * N + n] = double_to_bf16_rne((double)acc[m * N + n] * (double)sx[m] * (double)sw[n]);
+        for (int64_t n = 0; n < N; ++n) {
+            double v = (double)acc[m * N + n] * (double)sx[m] * (double)sw[n];
+            if (bias) v += bf16_to_double(bias[n]);
+            y[m * N + n] = double_to_bf16_rne(v);
+        }
     return ORACLE_OK;
 }
 
@@ -269,11 +278,13 @@ int oracle_rotquant(const uint16_t *x, int64_t rows, int64_t K, int g, int qmax,
 }
 
 /*
- * The whole ConvLinear4bit forward (Sec. 4.3) on bf16 X[M,K] and bf16 W[N,K]:
- * rotate + quantise both, integer GEMM, dequantise to bf16 Y[M,N].
+ * The whole ConvLinear forward (Sec. 4.3) on bf16 X[M,K] and bf16 W[N,K]: rotate + quantise both,
+ * integer GEMM, dequantise (+ optional bias) to bf16 Y[M,N].  qmax = 7 is ConvLinear4bit (W4A4);
+ * qmax = 127 is the W8A8 variant of the same layer (Sec. 5, Tables 5-2 and 5-4), read as the same
+ * symmetric quantiser with s = absmax / 127.
  */
-int oracle_convlinear4bit(const uint16_t *x, const uint16_t *w, int64_t M, int64_t N, int64_t K, int g,
-                          uint16_t *y)
+int oracle_convlinear(const uint16_t *x, const uint16_t *w, const uint16_t *bias, int64_t M, int64_t N, int64_t K,
+                      int g, int qmax, uint16_t *y)
 {
     if (!x || !w || !y || M < 0 || N < 0 || K <= 0) return ORACLE_ERR_ARG;
     size_t m1 = (size_t)(M > 0 ? M : 1), n1 = (size_t)(N > 0 ? N : 1);
@@ -282,10 +293,10 @@ int oracle_convlinear4bit(const uint16_t *x, const uint16_t *w, int64_t M, int64
     int32_t *acc = (int32_t *)malloc(sizeof(int32_t) * m1 * n1);
     int rc = ORACLE_ERR_ARG;
     if (qx && qw && sx && sw && acc) {
-        rc = oracle_rotquant(x, M, K, g, 7, qx, sx);
-        if (rc == ORACLE_OK) rc = oracle_rotquant(w, N, K, g, 7, qw, sw);
+        rc = oracle_rotquant(x, M, K, g, qmax, qx, sx);
+        if (rc == ORACLE_OK) rc = oracle_rotquant(w, N, K, g, qmax, qw, sw);
         if (rc == ORACLE_OK) rc = oracle_int_gemm(qx, qw, M, N, K, acc);
-        if (rc == ORACLE_OK) rc = oracle_dequant(acc, sx, sw, M, N, y);
+        if (rc == ORACLE_OK) rc = oracle_dequant(acc, sx, sw, bias, M, N, y);
     }
     free(qx); free(qw); free(sx); free(sw); free(acc);
     return rc;

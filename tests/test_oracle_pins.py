@@ -293,3 +293,64 @@ def test_outliers_hurt_and_rotation_helps():
     assert rel_err(clean, 16) < rel_err(dirty, 16)
     # larger groups spread a channel outlier over more channels (Sec. 4.2)
     assert rel_err(dirty, 256) < rel_err(dirty, 16) < rel_err(dirty, 4)
+
+
+# ----------------------------------------------------------------------------- bias and the W8A8 variant
+def test_dequant_bias_is_added_before_the_single_rounding():
+    acc = np.array([[3, -5], [0, 256]], dtype=np.int32)
+    sx = np.array([0.5, 2.0 ** -8], dtype=np.float32)
+    sw = np.array([0.25, 1.0], dtype=np.float32)
+    bias = bf16([1.0, 2.0 ** -8])
+    y = as_f64(oracle.dequant(acc, sx, sw, bias))
+    # [1,1]: 256 * 2^-8 * 1 + 2^-8 = 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1.0); rounding the
+    # product (1.0) and the sum separately could not tell, rounding the exact sum once does
+    # [0,1]: -2.5 + 2^-8 lies a quarter step (2^-6 in [2, 4)) from -2.5
+    assert np.array_equal(y, np.array([[1.375, -2.5], [1.0, 1.0]]))
+    # zero accumulators: the output is the bias itself; no bias: unchanged from the plain form
+    z = np.zeros((2, 2), dtype=np.int32)
+    assert np.array_equal(oracle.dequant(z, sx, sw, bias), np.tile(bias, (2, 1)))
+    assert np.array_equal(oracle.dequant(acc, sx, sw, None), oracle.dequant(acc, sx, sw))
+
+
+def test_forward_with_bias_on_representable_operands():
+    g, K, M, N = 16, 64, 3, 5
+    x = np.zeros((M, K), dtype=np.float32)
+    x[0], x[1], x[2] = 1.0, -2.0, 0.5
+    w = np.zeros((N, K), dtype=np.float32)
+    for n in range(N):
+        w[n, (n * 7) % K] = 0.25 * (n + 1)
+    # (no exact cancellation against the bias: the fp32 scales make acc * s_x * s_w exact only to ~2^-24)
+    b = np.array([0.75, -1.0, 0.0, 8.0, -0.125], dtype=np.float32)
+    y = as_f64(oracle.convlinear4bit(bf16(x), bf16(w), g, bias=bf16(b)))
+    assert np.array_equal(y, x.astype(np.float64) @ w.astype(np.float64).T + b[None, :])
+
+
+def test_eight_bit_quantiser_closed_forms_and_bound():
+    # same quantiser, 127 levels: one-hot row -> 127 * H[j] / ... only when sqrt(g) divides; use constant row
+    x = np.full((1, 64), -0.75, dtype=np.float32)
+    q, s = oracle.rotquant(bf16(x), 16, qmax=127)
+    assert (q == -127).all() and s[0] == np.float32(0.75 / 127)
+    rng = np.random.default_rng(3)
+    v = rng.standard_normal((7, 256))
+    q, s = oracle.quantize(v, qmax=127)
+    assert np.abs(q.astype(int)).max(axis=1).tolist() == [127] * 7
+    assert (np.abs(v - q * s[:, None].astype(np.float64)) <= s[:, None] / 2 * (1 + 1e-6)).all()
+    assert np.array_equal(s, (np.abs(v).max(axis=1) / 127).astype(np.float32))
+    # ties to even at 8 bits as at 4
+    t = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -126.5]])
+    q, s = oracle.quantize(t, qmax=127)
+    assert s[0] == 1.0 and q[0].tolist() == [127, 0, 2, 2, 0, -2, -126]
+
+
+def test_w8a8_forward_is_far_more_accurate_than_w4a4():
+    spec = wl.LayerSpec("pin_w8", M=32, K=512, N=24, group=16, x_col_count=0, x_row_count=0, seed=9)
+    x, w = wl.make_layer(spec)
+    ref = as_f64(x) @ as_f64(w).T
+    e4 = np.linalg.norm(as_f64(oracle.convlinear(x, w, 16, qmax=7)) - ref) / np.linalg.norm(ref)
+    e8 = np.linalg.norm(as_f64(oracle.convlinear(x, w, 16, qmax=127)) - ref) / np.linalg.norm(ref)
+    # uniform quantisation noise scales with the step: 127 / 7 = 18x finer
+    assert e8 < e4 / 8 and e8 < 0.02
+    qx, sx = oracle.rotquant(x, 16, qmax=127)
+    qw, sw = oracle.rotquant(w, 16, qmax=127)
+    assert np.array_equal(oracle.dequant(oracle.int_gemm(qx, qw), sx, sw), oracle.convlinear(x, w, 16, qmax=127))
+    assert np.array_equal(oracle.int_gemm(qx, qw), qx.astype(np.int64) @ qw.astype(np.int64).T)
