@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define CONVROT_VERSION 100          /* major*10000 + minor*100 + patch */
+#define CONVROT_VERSION 200          /* major*10000 + minor*100 + patch */
 #define CONVROT_MAX_K 65536          /* longest row the single-pass rotate+quantise kernel holds on chip */
 
 typedef enum convrot_status {
@@ -94,13 +94,17 @@ int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group,
 
 /*
  * W4A4 GEMM with the dequantisation fused (Sec. 4.3; suppl. Sec. B lists them as two stages):
- * Y[m,n] = bf16( (sum_k q_x[m,k] q_w[n,k]) * x_scale[m] * w_scale[n] ).
+ * Y[m,n] = bf16( (sum_k q_x[m,k] q_w[n,k]) * x_scale[m] * w_scale[n] + bias[n] ).
  *   Xq, Wq            DEVICE in   packed codes [M, K/2], [N, K/2]
  *   x_scale, w_scale  DEVICE in   [M], [N] fp32
+ *   bias_bf16         DEVICE in   [N] bf16, or NULL for none.  Eq. 10 of the paper has no bias; the
+ *                                 linear layers it replaces carry one, added here in fp32 before the
+ *                                 single rounding to bf16.  2-byte aligned.
  *   Y_bf16            DEVICE out  [M, N] bf16
  */
 int convrot_w4a4_gemm_dequant(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
-                              int64_t M, int64_t N, int64_t K, void *Y_bf16, void *stream);
+                              const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16,
+                              void *stream);
 
 /*
  * The whole ConvLinear4bit forward (Sec. 4.3): convrot_rotquant_act into the workspace, then
@@ -108,11 +112,12 @@ int convrot_w4a4_gemm_dequant(const void *Xq, const float *x_scale, const void *
  *   X_bf16     DEVICE in   [M, K] bf16
  *   Wq         DEVICE in   [N, K/2] from convrot_prepare_weight (same `group`)
  *   w_scale    DEVICE in   [N]
+ *   bias_bf16  DEVICE in   [N] bf16 or NULL, as above
  *   Y_bf16     DEVICE out  [M, N] bf16
  *   workspace  DEVICE scratch, 256-byte aligned, at least convrot_workspace_bytes(M, K) bytes;
  *              holds the activation codes and scales after the call.
  */
-int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_scale,
+int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16,
                            int64_t M, int64_t N, int64_t K, int group, void *Y_bf16,
                            void *workspace, size_t workspace_bytes, void *stream);
 

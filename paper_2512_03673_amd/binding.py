@@ -53,8 +53,8 @@ def load() -> ctypes.CDLL:
     lib.convrot_workspace_bytes.restype = sz
     lib.convrot_prepare_weight.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     lib.convrot_rotquant_act.argtypes = [vp, i64, i64, i32, vp, vp, vp]
-    lib.convrot_w4a4_gemm_dequant.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp]
-    lib.convlinear4bit_forward.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, sz, vp]
+    lib.convrot_w4a4_gemm_dequant.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
+    lib.convlinear4bit_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.convrot_w4a4_gemm_i32.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     for name in EXPORTS[4:]:
         getattr(lib, name).restype = i32
@@ -97,6 +97,13 @@ def _dev(t: torch.Tensor, dtype: torch.dtype, name: str) -> None:
         raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU")
 
 
+def _bias(b: Optional[torch.Tensor], N: int) -> None:
+    if b is not None:
+        _dev(b, torch.bfloat16, "bias")
+        if b.shape != (N,):
+            raise ValueError("bias: need shape [N]")
+
+
 def convrot_prepare_weight(W: torch.Tensor, group: int, Wq: Optional[torch.Tensor] = None,
                            w_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
     """W bf16 [N, K] -> (Wq uint8 [N, K/2], w_scale f32 [N])."""
@@ -122,8 +129,9 @@ def convrot_rotquant_act(X: torch.Tensor, group: int, Xq: Optional[torch.Tensor]
 
 
 def convrot_w4a4_gemm_dequant(Xq: torch.Tensor, x_scale: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor,
-                              Y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """Packed codes + scales -> Y bf16 [M, N]."""
+                              Y: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
+                              stream=None) -> torch.Tensor:
+    """Packed codes + scales (+ bias bf16 [N]) -> Y bf16 [M, N]."""
     _dev(Xq, torch.uint8, "Xq"); _dev(Wq, torch.uint8, "Wq")
     _dev(x_scale, torch.float32, "x_scale"); _dev(w_scale, torch.float32, "w_scale")
     M, Kb = Xq.shape
@@ -131,8 +139,9 @@ def convrot_w4a4_gemm_dequant(Xq: torch.Tensor, x_scale: torch.Tensor, Wq: torch
     if Kb != Kb2:
         raise ValueError("K mismatch")
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=Xq.device) if Y is None else Y
-    _check(load().convrot_w4a4_gemm_dequant(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), M, N, 2 * Kb,
-                                            _ptr(Y), _stream(stream)), "convrot_w4a4_gemm_dequant")
+    _bias(bias, N)
+    _check(load().convrot_w4a4_gemm_dequant(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N,
+                                            2 * Kb, _ptr(Y), _stream(stream)), "convrot_w4a4_gemm_dequant")
     return Y
 
 
@@ -152,7 +161,7 @@ def convrot_w4a4_gemm_i32(Xq: torch.Tensor, Wq: torch.Tensor, acc: Optional[torc
 
 def convlinear4bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor, group: int,
                            Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                           stream=None) -> torch.Tensor:
+                           bias: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """X bf16 [M, K], prepared weight -> Y bf16 [M, N]; `workspace` is a uint8 tensor of workspace_bytes(M, K)."""
     _dev(X, torch.bfloat16, "X"); _dev(Wq, torch.uint8, "Wq"); _dev(w_scale, torch.float32, "w_scale")
     M, K = X.shape
@@ -162,7 +171,8 @@ def convlinear4bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Ten
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if Y is None else Y
     if workspace is None:
         workspace = torch.empty((max(workspace_bytes(M, K), 256),), dtype=torch.uint8, device=X.device)
-    _check(load().convlinear4bit_forward(_ptr(X), _ptr(Wq), _ptr(w_scale), M, N, K, group, _ptr(Y),
+    _bias(bias, N)
+    _check(load().convlinear4bit_forward(_ptr(X), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K, group, _ptr(Y),
                                          _ptr(workspace), workspace.numel(), _stream(stream)),
            "convlinear4bit_forward")
     return Y

@@ -87,24 +87,25 @@ int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group, vo
 }
 
 int convrot_w4a4_gemm_dequant(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
-                              int64_t M, int64_t N, int64_t K, void *Y_bf16, void *stream)
+                              const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16, void *stream)
 {
     if (int rc = check_gemm(Xq, Wq, M, N, K, Y_bf16, 16)) return rc;
     if (missing(x_scale, M) || missing(w_scale, N)) return CONVROT_ERR_NULL;
-    if (!aligned(x_scale, 4) || !aligned(w_scale, 4)) return CONVROT_ERR_ALIGN;
-    return from_hip(convrot::launch_gemm_w4a4(Xq, x_scale, Wq, w_scale, M, N, K, Y_bf16, nullptr, (hipStream_t)stream));
+    if (!aligned(x_scale, 4) || !aligned(w_scale, 4) || !aligned(bias_bf16, 2)) return CONVROT_ERR_ALIGN;
+    return from_hip(convrot::launch_gemm_w4a4(Xq, x_scale, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr,
+                                              (hipStream_t)stream));
 }
 
 int convrot_w4a4_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K, int32_t *acc,
                           void *stream)
 {
     if (int rc = check_gemm(Xq, Wq, M, N, K, acc, 16)) return rc;
-    return from_hip(convrot::launch_gemm_w4a4(Xq, nullptr, Wq, nullptr, M, N, K, nullptr, acc, (hipStream_t)stream));
+    return from_hip(convrot::launch_gemm_w4a4(Xq, nullptr, Wq, nullptr, nullptr, M, N, K, nullptr, acc, (hipStream_t)stream));
 }
 
-int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_scale, int64_t M, int64_t N,
-                           int64_t K, int group, void *Y_bf16, void *workspace, size_t workspace_bytes,
-                           void *stream)
+int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16,
+                           int64_t M, int64_t N, int64_t K, int group, void *Y_bf16, void *workspace,
+                           size_t workspace_bytes, void *stream)
 {
     if (int rc = check_group(group)) return rc;
     if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
@@ -114,7 +115,7 @@ int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
         missing(workspace, M))
         return CONVROT_ERR_NULL;
     if (!aligned(X_bf16, 16) || !aligned(Wq, 16) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
-        !aligned(workspace, 256))
+        !aligned(bias_bf16, 2) || !aligned(workspace, 256))
         return CONVROT_ERR_ALIGN;
     if (workspace_bytes < convrot_workspace_bytes(M, K)) return CONVROT_ERR_WORKSPACE;
 
@@ -122,7 +123,7 @@ int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
     float *xs = reinterpret_cast<float *>(xq + round_up((size_t)M * (size_t)(K / 2), 256));
     hipStream_t s = (hipStream_t)stream;
     if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
-    return from_hip(convrot::launch_gemm_w4a4(xq, xs, Wq, w_scale, M, N, K, Y_bf16, nullptr, s));
+    return from_hip(convrot::launch_gemm_w4a4(xq, xs, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr, s));
 }
 
 }  // extern "C"

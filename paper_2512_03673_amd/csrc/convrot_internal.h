@@ -11,10 +11,10 @@ hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, vo
                            hipStream_t stream);
 
 // W4A4 GEMM on packed codes.  Exactly one of Y_bf16 / acc_i32 is non-null:
-//   Y_bf16 : dequantised bf16 output (needs x_scale, w_scale)
+//   Y_bf16 : dequantised bf16 output (needs x_scale, w_scale; bias_bf16 [N] or null)
 //   acc_i32: raw int32 accumulators
 hipError_t launch_gemm_w4a4(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
-                            int64_t M, int64_t N, int64_t K, void *Y_bf16, int32_t *acc_i32,
-                            hipStream_t stream);
+                            const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16,
+                            int32_t *acc_i32, hipStream_t stream);
 
 }  // namespace convrot

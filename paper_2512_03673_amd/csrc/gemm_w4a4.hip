@@ -63,7 +63,7 @@ constexpr int kRingBytes = kStages * kStageBytes;         // 72 KB
 constexpr int kChunks = kStageBytes / 1024 / 4;           // 1 KB LDS-direct loads per wavefront per stage: 6
 constexpr int kXChunks = TM * kRowBytes / 1024 / 4;       // ... of which the first 4 fetch X rows
 constexpr int kEpiPitch = WN * 2 + 16;                    // bf16 row of the wavefront tile + pad
-constexpr int kLdsTotal = kRingBytes + (TM + TN) * 4;     // + the tile's dequantisation scales
+constexpr int kLdsTotal = kRingBytes + (TM + 2 * TN) * 4; // + the tile's dequantisation scales and bias
 static_assert(kChunks * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
 static_assert(4 * 32 * kEpiPitch <= kRingBytes, "epilogue staging must fit the ring");
 static_assert(2 * kLdsTotal <= 160 * 1024, "two blocks per compute unit");
@@ -74,7 +74,8 @@ static_assert(kSubSteps == 2 && NF == 6, "slot plan of a K64 step");
 template <bool RAW>
 __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ x_scale, const uint8_t *__restrict__ Wq,
-    const float *__restrict__ w_scale, int M, int N, int K, uint16_t *__restrict__ Y,
+    const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
+    uint16_t *__restrict__ Y,
     int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -90,10 +91,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     // ---- dequantisation scales of the tile's rows and columns: thread t fetches x_scale[m0 + t] and
     // w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
     // the ring) once the loop is over.
-    float my_sx = 0.0f, my_sw = 0.0f;
+    float my_sx = 0.0f, my_sw = 0.0f, my_b = 0.0f;
     if constexpr (!RAW) {
         if (m0 + tid < M) my_sx = x_scale[m0 + tid];
-        if (tid < TN && n0 + tid < N) my_sw = w_scale[n0 + tid];
+        if (tid < TN && n0 + tid < N) {
+            my_sw = w_scale[n0 + tid];
+            if (bias) my_b = gemm::bf16_to_f32(bias[n0 + tid]);
+        }
     }
 
     // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
@@ -263,7 +267,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     } else {
         float *sx_lds = reinterpret_cast<float *>(lds + kRingBytes), *sw_lds = sx_lds + TM;
         sx_lds[tid] = my_sx * 0.00390625f;   // 2^-8 undoes the 16 * 16 of the widening
-        if (tid < TN) sw_lds[tid] = my_sw;
+        if (tid < TN) {
+            sw_lds[tid] = my_sw;
+            sw_lds[TN + tid] = my_b;
+        }
         __syncthreads();     // every wavefront has finished reading the ring; the scales are visible
         // `interior`: the tile lies wholly inside Y and rows of Y are 16-byte multiples, so the stores need
         // no bounds checks (uniform over the block).
@@ -280,7 +287,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
         for (int i = 0; i < XF; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
         uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x 64 bf16 staging tile
         const int ncol = n0 + wn0 + (lane & 7) * 8;              // first of this lane's 8 output columns
-        auto body = [&](auto INTERIOR) {
+        auto body = [&](auto INTERIOR, auto BIAS) {
 #pragma unroll
             for (int i = 0; i < XF; ++i) {
                 const int mrow = m0 + wm0 + i * 32;
@@ -290,7 +297,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
                     for (int rb = 0; rb < 4; ++rb) {
                         float y[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) y[e] = ((float)acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
+                        for (int e = 0; e < 4; ++e) {
+                            y[e] = ((float)acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
+                            if constexpr (decltype(BIAS)::value) y[e] += sw_lds[TN + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4 + e];
+                        }
                         const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
                         *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
                             make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
@@ -318,15 +328,21 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
                 }
             }
         };
-        if (interior) body(std::true_type{});
-        else body(std::false_type{});
+        if (bias) {
+            if (interior) body(std::true_type{}, std::true_type{});
+            else body(std::false_type{}, std::true_type{});
+        } else {
+            if (interior) body(std::true_type{}, std::false_type{});
+            else body(std::false_type{}, std::false_type{});
+        }
     }
 }
 
 namespace {
 
 template <bool RAW>
-hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, int M, int N, int K,
+hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, const void *bias,
+                      int M, int N, int K,
                       void *Y, int32_t *acc, hipStream_t stream)
 {
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
@@ -340,22 +356,24 @@ hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, cons
         attr_done = true;
     }
     hipLaunchKernelGGL((gemm_w4a4_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsTotal, stream, (const uint8_t *)Xq,
-                       x_scale, (const uint8_t *)Wq, w_scale, M, N, K, (uint16_t *)Y, acc, tiles_m, tiles_n);
+                       x_scale, (const uint8_t *)Wq, w_scale, (const uint16_t *)bias, M, N, K, (uint16_t *)Y, acc, tiles_m,
+                       tiles_n);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_gemm_w4a4(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
-                            int64_t M, int64_t N, int64_t K, void *Y_bf16, int32_t *acc_i32,
-                            hipStream_t stream)
+                            const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16,
+                            int32_t *acc_i32, hipStream_t stream)
 {
     if (M == 0 || N == 0) return hipSuccess;
     if (K % (2 * kRowBytes) != 0)   // a ragged last stage: the general kernel zero-fills it
-        return launch_gemm_w4a4_generic(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, Y_bf16, acc_i32, stream);
+        return launch_gemm_w4a4_generic(Xq, x_scale, Wq, w_scale, bias_bf16, (int)M, (int)N, (int)K, Y_bf16, acc_i32,
+                                        stream);
     if (acc_i32)
-        return launch_one<true>(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, nullptr, acc_i32, stream);
-    return launch_one<false>(Xq, x_scale, Wq, w_scale, (int)M, (int)N, (int)K, Y_bf16, nullptr, stream);
+        return launch_one<true>(Xq, x_scale, Wq, w_scale, nullptr, (int)M, (int)N, (int)K, nullptr, acc_i32, stream);
+    return launch_one<false>(Xq, x_scale, Wq, w_scale, bias_bf16, (int)M, (int)N, (int)K, Y_bf16, nullptr, stream);
 }
 
 }  // namespace convrot

@@ -65,6 +65,8 @@ __device__ __forceinline__ void lds_dma4_addr(const void *lane_ptr, uint32_t lds
                  :: "v"(lane_ptr), "s"(lds_addr) : "memory");
 }
 
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
 {
     v2bf r = __builtin_convertvector((v2f){a, b}, v2bf);   // v_cvt_pk_bf16_f32: round to nearest even
@@ -96,6 +98,7 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
 
 // One output tile per block, any K the library accepts (gemm_w4a4_generic.hip).
 hipError_t launch_gemm_w4a4_generic(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
-                                    int M, int N, int K, void *Y_bf16, int32_t *acc_i32, hipStream_t stream);
+                                    const void *bias_bf16, int M, int N, int K, void *Y_bf16, int32_t *acc_i32,
+                                    hipStream_t stream);
 
 }  // namespace convrot

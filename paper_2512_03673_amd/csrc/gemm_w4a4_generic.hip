@@ -12,7 +12,7 @@ using namespace gemm;
 namespace {
 
 constexpr int kLdsBytes = kRingBytes;
-constexpr int kLdsTotal = kLdsBytes + (BM + BN) * 4;      // + the tile's dequantisation scales
+constexpr int kLdsTotal = kLdsBytes + (BM + 2 * BN) * 4;  // + the tile's dequantisation scales and bias
 constexpr int kEpiPitch = WTN * 2 + 16;                   // bf16 row of the wavefront tile + pad
 static_assert(4 * 32 * kEpiPitch <= kLdsBytes, "epilogue staging must fit the ring");
 static_assert(kLdsTotal <= 160 * 1024, "LDS");
@@ -25,7 +25,8 @@ __device__ const uint4 kZeroPiece = {0u, 0u, 0u, 0u};
 template <bool RAW>
 __global__ __launch_bounds__(kThreads) void gemm_w4a4_generic_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ x_scale, const uint8_t *__restrict__ Wq,
-    const float *__restrict__ w_scale, int M, int N, int K, uint16_t *__restrict__ Y,
+    const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
+    uint16_t *__restrict__ Y,
     int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -195,10 +196,13 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_generic_kernel(
     // ---- dequantisation scales of the tile's 256 rows and 256 columns: thread t fetches x_scale[m0 + t]
     // and w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
     // the ring) once the loop is over.
-    float my_sx = 0.0f, my_sw = 0.0f;
+    float my_sx = 0.0f, my_sw = 0.0f, my_b = 0.0f;
     if constexpr (!RAW) {
         if (m0 + tid < M) my_sx = x_scale[m0 + tid];
-        if (n0 + tid < N) my_sw = w_scale[n0 + tid];
+        if (n0 + tid < N) {
+            my_sw = w_scale[n0 + tid];
+            if (bias) my_b = bf16_to_f32(bias[n0 + tid]);
+        }
     }
 
     // ---- pipeline: stages 0 .. S-2 are in flight before the loop (stages past the end of K are dummy
@@ -277,6 +281,7 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_generic_kernel(
         float *sx_lds = reinterpret_cast<float *>(lds + kLdsBytes), *sw_lds = sx_lds + BM;
         sx_lds[tid] = my_sx * 0.00390625f;   // 2^-8 undoes the 16 * 16 of the widening
         sw_lds[tid] = my_sw;
+        sw_lds[BN + tid] = my_b;
         __syncthreads();     // every wavefront has finished reading the ring; the scales are visible
         // `interior`: the tile lies wholly inside Y and rows of Y are 16-byte multiples, so the stores need
         // no bounds checks (uniform over the block).
@@ -294,7 +299,7 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_generic_kernel(
         for (int i = 0; i < FM; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
         uint8_t *stage = lds + wave * (32 * kEpiPitch);     // this wavefront's 32 x 128 bf16 staging tile
         const int ncol = n0 + wn0 + (lane & 15) * 8;         // first of this lane's 8 output columns
-        auto body = [&](auto INTERIOR) {
+        auto body = [&](auto INTERIOR, auto BIAS) {
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 const int mrow = m0 + wm0 + i * 32;
@@ -304,7 +309,10 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_generic_kernel(
                     for (int rb = 0; rb < 4; ++rb) {
                         float y[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) y[e] = ((float)acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
+                        for (int e = 0; e < 4; ++e) {
+                            y[e] = ((float)acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
+                            if constexpr (decltype(BIAS)::value) y[e] += sw_lds[BN + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4 + e];
+                        }
                         const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
                         *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
                             make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
@@ -332,15 +340,21 @@ __global__ __launch_bounds__(kThreads) void gemm_w4a4_generic_kernel(
                 }
             }
         };
-        if (interior) body(std::true_type{});
-        else body(std::false_type{});
+        if (bias) {
+            if (interior) body(std::true_type{}, std::true_type{});
+            else body(std::false_type{}, std::true_type{});
+        } else {
+            if (interior) body(std::true_type{}, std::false_type{});
+            else body(std::false_type{}, std::false_type{});
+        }
     }
 }
 
 namespace {
 
 template <bool RAW>
-hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, int M, int N, int K,
+hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, const void *bias,
+                      int M, int N, int K,
                       void *Y, int32_t *acc, hipStream_t stream)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
@@ -354,17 +368,19 @@ hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, cons
         attr_done = true;
     }
     hipLaunchKernelGGL((gemm_w4a4_generic_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsTotal, stream, (const uint8_t *)Xq,
-                       x_scale, (const uint8_t *)Wq, w_scale, M, N, K, (uint16_t *)Y, acc, tiles_m, tiles_n);
+                       x_scale, (const uint8_t *)Wq, w_scale, (const uint16_t *)bias, M, N, K, (uint16_t *)Y, acc, tiles_m,
+                       tiles_n);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_gemm_w4a4_generic(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
-                                    int M, int N, int K, void *Y_bf16, int32_t *acc_i32, hipStream_t stream)
+                                    const void *bias_bf16, int M, int N, int K, void *Y_bf16, int32_t *acc_i32,
+                                    hipStream_t stream)
 {
-    if (acc_i32) return launch_one<true>(Xq, x_scale, Wq, w_scale, M, N, K, nullptr, acc_i32, stream);
-    return launch_one<false>(Xq, x_scale, Wq, w_scale, M, N, K, Y_bf16, nullptr, stream);
+    if (acc_i32) return launch_one<true>(Xq, x_scale, Wq, w_scale, nullptr, M, N, K, nullptr, acc_i32, stream);
+    return launch_one<false>(Xq, x_scale, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr, stream);
 }
 
 }  // namespace convrot

@@ -21,7 +21,7 @@ import numpy as np
 
 __all__ = [
     "f32_to_bf16_bits", "bf16_bits_to_f32", "LayerSpec", "make_activation",
-    "make_weight", "make_layer", "CONFIGS", "layers_of_config",
+    "make_weight", "make_bias", "make_layer", "CONFIGS", "NEXT_CONFIGS", "layers_of_config",
 ]
 
 
@@ -109,6 +109,12 @@ def make_weight(spec: LayerSpec, rows: Optional[int] = None) -> np.ndarray:
     return f32_to_bf16_bits(w)
 
 
+def make_bias(spec: LayerSpec) -> np.ndarray:
+    """Bias as bf16 bits, shape [N]: N(0, 0.1).  (The paper's Eq. 10 has no bias; the linear layers it replaces do.)"""
+    rng = _rng(spec.seed, "B:" + spec.name)
+    return f32_to_bf16_bits(rng.standard_normal(size=(spec.N,), dtype=np.float32) * np.float32(0.1))
+
+
 def make_layer(spec: LayerSpec) -> Tuple[np.ndarray, np.ndarray]:
     return make_activation(spec), make_weight(spec)
 
@@ -141,6 +147,12 @@ CONFIGS: Dict[str, Tuple[LayerSpec, ...]] = {
 }
 
 HEADLINE = CONFIGS["cfg3_mlp"][0]
+
+# Shapes beyond the five configurations: the fused-width layer the paper itself profiles (supplement
+# Sec. B: X [1 x 4608 x 15360], W [3072 x 15360]), run with a bias.
+NEXT_CONFIGS: Dict[str, Tuple[LayerSpec, ...]] = {
+    "n1_fused_width": (_flux("fused_out", 4608, 15360, 3072, x_kind="halfnormal"),),
+}
 
 
 def layers_of_config(name: str) -> Tuple[LayerSpec, ...]:

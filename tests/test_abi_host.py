@@ -36,7 +36,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_size_queries_and_strings(lib):
     from paper_2512_03673_amd import binding as b
-    assert b.version() == 100
+    assert b.version() == 200
     assert b.packed_bytes(4608, 3072) == 4608 * 1536
     assert b.packed_bytes(-1, 32) == 0 and b.packed_bytes(4, 33) == 0
     # codes rounded up to 256 B + scales rounded up to 256 B

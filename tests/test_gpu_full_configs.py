@@ -19,6 +19,8 @@ from paper_2512_03673_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 FULL = [spec for cfg in ("cfg2_qkv", "cfg3_mlp", "cfg4_group_sweep", "cfg5_hires") for spec in wl.CONFIGS[cfg]]
+FULL += list(wl.NEXT_CONFIGS["n1_fused_width"])     # run with a bias
+WITH_BIAS = {"fused_out"}
 
 
 @pytest.fixture(scope="module")
@@ -48,7 +50,8 @@ def test_full_size_layer(cr, spec):
     wq, ws = cr.convrot_prepare_weight(to_dev_bf16(w), g)
     ws_buf = torch.empty((cr.workspace_bytes(spec.M, spec.K),), dtype=torch.uint8, device="cuda")
     y = torch.empty((spec.M, spec.N), dtype=torch.bfloat16, device="cuda")
-    cr.convlinear4bit_forward(xd, wq, ws, g, y, ws_buf)
+    bias = wl.make_bias(spec) if spec.name in WITH_BIAS else None
+    cr.convlinear4bit_forward(xd, wq, ws, g, y, ws_buf, bias=None if bias is None else to_dev_bf16(bias))
     xq, xs = cr.convrot_rotquant_act(xd, g)
     torch.cuda.synchronize()
     # the fused call leaves the activation codes and scales in its workspace: same bytes as the stand-alone call
@@ -78,11 +81,11 @@ def test_full_size_layer(cr, spec):
     torch.cuda.synchronize()
     assert np.array_equal(acc_g.cpu().numpy(), acc_o), f"{spec.name}: int32 GEMM differs"
 
-    y_o = oracle.dequant(oracle.int_gemm(qxo[rows], qwo), sxo[rows], swo)
+    y_o = oracle.dequant(oracle.int_gemm(qxo[rows], qwo), sxo[rows], swo, bias)
     y_g = bf16_to_host_bits(y[rt])
     rel, cos = check_output(y_g, y_o, spec.name)
     same_rows = (qxg[rows] == qxo[rows]).all(axis=1)
-    if fw == 1.0 and same_rows.any():
+    if fw == 1.0 and same_rows.any() and bias is None:
         d = bf16_ulp_diff(y_g[same_rows], y_o[same_rows])
         assert d.max() <= 1, f"{spec.name}: output {d.max()} bf16 steps off on identical codes"
     assert torch.isfinite(y.float()).all()

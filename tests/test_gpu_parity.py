@@ -117,6 +117,40 @@ def test_gemm_dequant_on_identical_codes(cr, M, N, K):
     check_output(yb, yo, "dequant")
 
 
+@pytest.mark.parametrize("M,N,K", [(300, 520, 1024), (129, 1026, 3072), (31, 5, 64), (260, 136, 96)])
+def test_gemm_dequant_with_bias(cr, M, N, K):
+    rng = np.random.default_rng(M * N + K)
+    qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    sx = np.exp(rng.uniform(-6, 2, M)).astype(np.float32)
+    sw = np.exp(rng.uniform(-9, -4, N)).astype(np.float32)
+    bias = wl.f32_to_bf16_bits((rng.standard_normal(N) * 0.5).astype(np.float32))
+    y = cr.convrot_w4a4_gemm_dequant(torch.from_numpy(oracle.pack4(qx)).cuda(), torch.from_numpy(sx).cuda(),
+                                     torch.from_numpy(oracle.pack4(qw)).cuda(), torch.from_numpy(sw).cuda(),
+                                     bias=to_dev_bf16(bias))
+    torch.cuda.synchronize()
+    yb = bf16_to_host_bits(y)
+    yo = oracle.dequant(oracle.int_gemm(qx, qw), sx, sw, bias)
+    # fp32 (acc*sx)*sw + b then one rounding vs the exact sum: at most one bf16 step (relative to the larger of
+    # the output and the bias where the two cancel), almost always none
+    d = bf16_ulp_diff(yb, yo)
+    assert (d == 0).mean() > 0.995
+    err = np.abs(bits_to_f64(yb) - bits_to_f64(yo))
+    mag = np.maximum(np.abs(bits_to_f64(yo)), np.abs(bits_to_f64(bias))[None, :])
+    assert (err <= mag * 2.0 ** -7).all()
+    check_output(yb, yo, "dequant+bias")
+
+
+def test_forward_with_bias_matches_oracle(cr):
+    spec = wl.LayerSpec("fwd_bias", M=300, K=1024, N=520, group=16, seed=4)
+    x, w = wl.make_layer(spec)
+    bias = wl.make_bias(spec)
+    wq, ws = cr.convrot_prepare_weight(to_dev_bf16(w), 16)
+    y = cr.convlinear4bit_forward(to_dev_bf16(x), wq, ws, 16, bias=to_dev_bf16(bias))
+    torch.cuda.synchronize()
+    check_output(bf16_to_host_bits(y), oracle.convlinear4bit(x, w, 16, bias=bias), "forward+bias")
+
+
 # ------------------------------------------------------------------ whole forward
 @pytest.mark.parametrize("g", (4, 16, 64, 256))
 def test_forward_tiny_config(cr, g):
@@ -194,7 +228,7 @@ def test_error_statuses_write_nothing(cr):
     y = torch.empty((4, 8), dtype=torch.bfloat16, device=dev)
     wq = torch.zeros((8, 512), dtype=torch.uint8, device=dev)
     wsc = torch.ones((8,), dtype=torch.float32, device=dev)
-    assert lib.convlinear4bit_forward(x.data_ptr(), wq.data_ptr(), wsc.data_ptr(), 4, 8, 1024, 16, y.data_ptr(),
+    assert lib.convlinear4bit_forward(x.data_ptr(), wq.data_ptr(), wsc.data_ptr(), None, 4, 8, 1024, 16, y.data_ptr(),
                                       ws.data_ptr(), 256, None) == -5
     torch.cuda.synchronize()
     assert (q == 0xAB).all() and (s == 5.0).all()
