@@ -68,23 +68,25 @@ def test_argument_validation_without_a_device(lib):
     assert p(None, 4, 1024, 16, A, A, None) == -1
     assert p(A, 4, 1024, 3, A, A, None) == -3
     g = lib.convrot_w4a4_gemm_dequant
-    assert g(None, A, A, A, 4, 4, 1024, A, None) == -1
-    assert g(A, None, A, A, 4, 4, 1024, A, None) == -1
-    assert g(A, A, A, A, 4, -4, 1024, A, None) == -2
-    assert g(A, A, A, A, 4, 4, 1000, A, None) == -2
-    assert g(A, A, A + 1, A, 4, 4, 1024, A, None) == -4
+    assert g(None, A, A, A, None, 4, 4, 1024, A, None) == -1
+    assert g(A, None, A, A, None, 4, 4, 1024, A, None) == -1
+    assert g(A, A, A, A, None, 4, -4, 1024, A, None) == -2
+    assert g(A, A, A, A, A, 4, 4, 1000, A, None) == -2
+    assert g(A, A, A + 1, A, None, 4, 4, 1024, A, None) == -4
+    assert g(A, A, A, A, A + 1, 4, 4, 1024, A, None) == -4      # bias is bf16: 2-byte aligned
     r = lib.convrot_w4a4_gemm_i32
     assert r(A, A, 4, 4, 1024, None, None) == -1
     assert r(A, A, 4, 4, 48, A, None) == -2
     fw = lib.convlinear4bit_forward
-    assert fw(A, A, A, 4, 4, 1024, 16, A, None, 1 << 20, None) == -1
-    assert fw(A, A, A, 4, 4, 1024, 5, A, A, 1 << 20, None) == -3
-    assert fw(A, A, A, 4, 4, 1024, 16, A, A + 16, 1 << 20, None) == -4
-    assert fw(A, A, A, 4, 4, 1024, 16, A, A, 100, None) == -5
+    assert fw(A, A, A, None, 4, 4, 1024, 16, A, None, 1 << 20, None) == -1
+    assert fw(A, A, A, None, 4, 4, 1024, 5, A, A, 1 << 20, None) == -3
+    assert fw(A, A, A, A, 4, 4, 1024, 16, A, A + 16, 1 << 20, None) == -4
+    assert fw(A, A, A, A + 1, 4, 4, 1024, 16, A, A, 1 << 20, None) == -4
+    assert fw(A, A, A, None, 4, 4, 1024, 16, A, A, 100, None) == -5
     # empty problems are valid no-ops and launch nothing
     assert f(A, 0, 1024, 16, A, A, None) == 0
-    assert g(A, A, A, A, 0, 4, 1024, A, None) == 0
-    assert g(A, A, A, A, 4, 0, 1024, A, None) == 0
+    assert g(A, A, A, A, None, 0, 4, 1024, A, None) == 0
+    assert g(A, A, A, A, A, 4, 0, 1024, A, None) == 0
 
 
 def test_product_package_does_not_import_the_oracle():
