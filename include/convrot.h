@@ -129,6 +129,37 @@ int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
 int convrot_w4a4_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K,
                           int32_t *acc, void *stream);
 
+/*
+ * ---- W8A8 variant of the layer (the paper's W8A8 rows, Sec. 5, Tables 5-2 and 5-4, and the ~20 % of
+ * layers its mixed-precision mode keeps at 8 bits): the same rotation, the same symmetric quantiser
+ * with 127 levels (s = a / 127, q in [-127, 127]), int8 codes stored one per byte, row-major [rows, K].
+ * Everything said above about pointers, streams, errors and shapes holds, with K % 64 == 0 in
+ * addition (CONVROT_ERR_SHAPE otherwise).
+ */
+
+/* Host.  Workspace of convlinear8bit_forward: int8 codes [M, K] (rounded up to 256 bytes) + M fp32 scales. */
+size_t convrot_workspace_bytes8(int64_t M, int64_t K);
+
+/* As convrot_prepare_weight / convrot_rotquant_act, 8-bit: Wq, Xq are [rows, K] int8. */
+int convrot_prepare_weight8(const void *W_bf16, int64_t N, int64_t K, int group,
+                            void *Wq, float *w_scale, void *stream);
+int convrot_rotquant_act8(const void *X_bf16, int64_t M, int64_t K, int group,
+                          void *Xq, float *x_scale, void *stream);
+
+/* As convrot_w4a4_gemm_dequant on int8 codes [M, K], [N, K]. */
+int convrot_w8a8_gemm_dequant(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
+                              const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16,
+                              void *stream);
+
+/* As convlinear4bit_forward with 8-bit codes; workspace of convrot_workspace_bytes8(M, K) bytes. */
+int convlinear8bit_forward(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16,
+                           int64_t M, int64_t N, int64_t K, int group, void *Y_bf16,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Gate / debug export: raw int32 accumulators of the 8-bit GEMM. */
+int convrot_w8a8_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K,
+                          int32_t *acc, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,9 @@ STATUS_NAMES = {0: "CONVROT_OK", -1: "CONVROT_ERR_NULL", -2: "CONVROT_ERR_SHAPE"
 # every symbol include/convrot.h declares
 EXPORTS = ("convrot_status_string", "convrot_version", "convrot_packed_bytes", "convrot_workspace_bytes",
            "convrot_prepare_weight", "convrot_rotquant_act", "convrot_w4a4_gemm_dequant",
-           "convlinear4bit_forward", "convrot_w4a4_gemm_i32")
+           "convlinear4bit_forward", "convrot_w4a4_gemm_i32",
+           "convrot_prepare_weight8", "convrot_rotquant_act8", "convrot_w8a8_gemm_dequant",
+           "convlinear8bit_forward", "convrot_w8a8_gemm_i32", "convrot_workspace_bytes8")
 
 _lib = None
 
@@ -56,7 +58,14 @@ def load() -> ctypes.CDLL:
     lib.convrot_w4a4_gemm_dequant.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
     lib.convlinear4bit_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.convrot_w4a4_gemm_i32.argtypes = [vp, vp, i64, i64, i64, vp, vp]
-    for name in EXPORTS[4:]:
+    lib.convrot_workspace_bytes8.argtypes = [i64, i64]
+    lib.convrot_workspace_bytes8.restype = sz
+    lib.convrot_prepare_weight8.argtypes = lib.convrot_prepare_weight.argtypes
+    lib.convrot_rotquant_act8.argtypes = lib.convrot_rotquant_act.argtypes
+    lib.convrot_w8a8_gemm_dequant.argtypes = lib.convrot_w4a4_gemm_dequant.argtypes
+    lib.convlinear8bit_forward.argtypes = lib.convlinear4bit_forward.argtypes
+    lib.convrot_w8a8_gemm_i32.argtypes = lib.convrot_w4a4_gemm_i32.argtypes
+    for name in EXPORTS[4:-1]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -76,6 +85,10 @@ def packed_bytes(rows: int, K: int) -> int:
 
 def workspace_bytes(M: int, K: int) -> int:
     return int(load().convrot_workspace_bytes(M, K))
+
+
+def workspace_bytes8(M: int, K: int) -> int:
+    return int(load().convrot_workspace_bytes8(M, K))
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
@@ -175,4 +188,76 @@ def convlinear4bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Ten
     _check(load().convlinear4bit_forward(_ptr(X), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K, group, _ptr(Y),
                                          _ptr(workspace), workspace.numel(), _stream(stream)),
            "convlinear4bit_forward")
+    return Y
+
+
+# ---------------------------------------------------------------------------- W8A8 variant
+def _rotquant8(fn_name: str, X: torch.Tensor, group: int, Xq, x_scale, stream):
+    _dev(X, torch.bfloat16, "input")
+    rows, K = X.shape
+    Xq = torch.empty((rows, K), dtype=torch.int8, device=X.device) if Xq is None else Xq
+    x_scale = torch.empty((rows,), dtype=torch.float32, device=X.device) if x_scale is None else x_scale
+    _check(getattr(load(), fn_name)(_ptr(X), rows, K, group, _ptr(Xq), _ptr(x_scale), _stream(stream)), fn_name)
+    return Xq, x_scale
+
+
+def convrot_prepare_weight8(W: torch.Tensor, group: int, Wq: Optional[torch.Tensor] = None,
+                            w_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """W bf16 [N, K] -> (Wq int8 [N, K], w_scale f32 [N])."""
+    return _rotquant8("convrot_prepare_weight8", W, group, Wq, w_scale, stream)
+
+
+def convrot_rotquant_act8(X: torch.Tensor, group: int, Xq: Optional[torch.Tensor] = None,
+                          x_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """X bf16 [M, K] -> (Xq int8 [M, K], x_scale f32 [M])."""
+    return _rotquant8("convrot_rotquant_act8", X, group, Xq, x_scale, stream)
+
+
+def convrot_w8a8_gemm_dequant(Xq: torch.Tensor, x_scale: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor,
+                              Y: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
+                              stream=None) -> torch.Tensor:
+    """int8 codes + scales (+ bias bf16 [N]) -> Y bf16 [M, N]."""
+    _dev(Xq, torch.int8, "Xq"); _dev(Wq, torch.int8, "Wq")
+    _dev(x_scale, torch.float32, "x_scale"); _dev(w_scale, torch.float32, "w_scale")
+    M, K = Xq.shape
+    N, K2 = Wq.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=Xq.device) if Y is None else Y
+    _bias(bias, N)
+    _check(load().convrot_w8a8_gemm_dequant(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K,
+                                            _ptr(Y), _stream(stream)), "convrot_w8a8_gemm_dequant")
+    return Y
+
+
+def convrot_w8a8_gemm_i32(Xq: torch.Tensor, Wq: torch.Tensor, acc: Optional[torch.Tensor] = None,
+                          stream=None) -> torch.Tensor:
+    """int8 codes -> raw int32 accumulators [M, N] (gate / debug export)."""
+    _dev(Xq, torch.int8, "Xq"); _dev(Wq, torch.int8, "Wq")
+    M, K = Xq.shape
+    N, K2 = Wq.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    acc = torch.empty((M, N), dtype=torch.int32, device=Xq.device) if acc is None else acc
+    _check(load().convrot_w8a8_gemm_i32(_ptr(Xq), _ptr(Wq), M, N, K, _ptr(acc), _stream(stream)),
+           "convrot_w8a8_gemm_i32")
+    return acc
+
+
+def convlinear8bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor, group: int,
+                           Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                           bias: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """X bf16 [M, K], prepared 8-bit weight -> Y bf16 [M, N]; `workspace`: uint8 tensor of workspace_bytes8(M, K)."""
+    _dev(X, torch.bfloat16, "X"); _dev(Wq, torch.int8, "Wq"); _dev(w_scale, torch.float32, "w_scale")
+    M, K = X.shape
+    N = Wq.shape[0]
+    if Wq.shape[1] != K:
+        raise ValueError("K mismatch")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if Y is None else Y
+    if workspace is None:
+        workspace = torch.empty((max(workspace_bytes8(M, K), 256),), dtype=torch.uint8, device=X.device)
+    _bias(bias, N)
+    _check(load().convlinear8bit_forward(_ptr(X), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K, group, _ptr(Y),
+                                         _ptr(workspace), workspace.numel(), _stream(stream)),
+           "convlinear8bit_forward")
     return Y

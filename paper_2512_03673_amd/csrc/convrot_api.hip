@@ -49,7 +49,7 @@ const char *convrot_status_string(int status)
     switch (status) {
         case CONVROT_OK: return "ok";
         case CONVROT_ERR_NULL: return "null pointer";
-        case CONVROT_ERR_SHAPE: return "bad shape (need M,N >= 0, 0 < K <= 65536, K % 32 == 0, K % group == 0)";
+        case CONVROT_ERR_SHAPE: return "bad shape (need M,N >= 0, 0 < K <= 65536, K % 32 == 0 (8-bit: K % 64 == 0), K % group == 0)";
         case CONVROT_ERR_GROUP: return "bad group size (need 4, 16, 64, 256 or 1024)";
         case CONVROT_ERR_ALIGN: return "misaligned pointer";
         case CONVROT_ERR_WORKSPACE: return "workspace too small";
@@ -76,14 +76,14 @@ int convrot_prepare_weight(const void *W_bf16, int64_t N, int64_t K, int group, 
                            void *stream)
 {
     if (int rc = check_rotquant(W_bf16, N, K, group, Wq, w_scale)) return rc;
-    return from_hip(convrot::launch_rotquant(W_bf16, N, K, group, Wq, w_scale, (hipStream_t)stream));
+    return from_hip(convrot::launch_rotquant(W_bf16, N, K, group, 4, Wq, w_scale, (hipStream_t)stream));
 }
 
 int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group, void *Xq, float *x_scale,
                          void *stream)
 {
     if (int rc = check_rotquant(X_bf16, M, K, group, Xq, x_scale)) return rc;
-    return from_hip(convrot::launch_rotquant(X_bf16, M, K, group, Xq, x_scale, (hipStream_t)stream));
+    return from_hip(convrot::launch_rotquant(X_bf16, M, K, group, 4, Xq, x_scale, (hipStream_t)stream));
 }
 
 int convrot_w4a4_gemm_dequant(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
@@ -122,8 +122,75 @@ int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
     uint8_t *xq = static_cast<uint8_t *>(workspace);
     float *xs = reinterpret_cast<float *>(xq + round_up((size_t)M * (size_t)(K / 2), 256));
     hipStream_t s = (hipStream_t)stream;
-    if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
+    if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, 4, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
     return from_hip(convrot::launch_gemm_w4a4(xq, xs, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr, s));
+}
+
+// ---- W8A8 variant
+
+size_t convrot_workspace_bytes8(int64_t M, int64_t K)
+{
+    if (M < 0 || K <= 0) return 0;
+    return round_up((size_t)M * (size_t)K, 256) + round_up((size_t)M * sizeof(float), 256);
+}
+
+int convrot_prepare_weight8(const void *W_bf16, int64_t N, int64_t K, int group, void *Wq, float *w_scale,
+                            void *stream)
+{
+    if (int rc = check_rotquant(W_bf16, N, K, group, Wq, w_scale)) return rc;
+    if (K % 64 != 0) return CONVROT_ERR_SHAPE;
+    return from_hip(convrot::launch_rotquant(W_bf16, N, K, group, 8, Wq, w_scale, (hipStream_t)stream));
+}
+
+int convrot_rotquant_act8(const void *X_bf16, int64_t M, int64_t K, int group, void *Xq, float *x_scale,
+                          void *stream)
+{
+    if (int rc = check_rotquant(X_bf16, M, K, group, Xq, x_scale)) return rc;
+    if (K % 64 != 0) return CONVROT_ERR_SHAPE;
+    return from_hip(convrot::launch_rotquant(X_bf16, M, K, group, 8, Xq, x_scale, (hipStream_t)stream));
+}
+
+int convrot_w8a8_gemm_dequant(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
+                              const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16, void *stream)
+{
+    if (int rc = check_gemm(Xq, Wq, M, N, K, Y_bf16, 16)) return rc;
+    if (K % 64 != 0) return CONVROT_ERR_SHAPE;
+    if (missing(x_scale, M) || missing(w_scale, N)) return CONVROT_ERR_NULL;
+    if (!aligned(x_scale, 4) || !aligned(w_scale, 4) || !aligned(bias_bf16, 2)) return CONVROT_ERR_ALIGN;
+    return from_hip(convrot::launch_gemm_w8a8(Xq, x_scale, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr,
+                                              (hipStream_t)stream));
+}
+
+int convrot_w8a8_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K, int32_t *acc,
+                          void *stream)
+{
+    if (int rc = check_gemm(Xq, Wq, M, N, K, acc, 16)) return rc;
+    if (K % 64 != 0) return CONVROT_ERR_SHAPE;
+    return from_hip(convrot::launch_gemm_w8a8(Xq, nullptr, Wq, nullptr, nullptr, M, N, K, nullptr, acc,
+                                              (hipStream_t)stream));
+}
+
+int convlinear8bit_forward(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16,
+                           int64_t M, int64_t N, int64_t K, int group, void *Y_bf16, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_group(group)) return rc;
+    if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
+    if (int rc = check_k(K)) return rc;
+    if (K % group != 0 || K % 64 != 0) return CONVROT_ERR_SHAPE;
+    if (missing(X_bf16, M) || missing(Wq, N) || missing(w_scale, N) || missing(Y_bf16, M * N) ||
+        missing(workspace, M))
+        return CONVROT_ERR_NULL;
+    if (!aligned(X_bf16, 16) || !aligned(Wq, 16) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
+        !aligned(bias_bf16, 2) || !aligned(workspace, 256))
+        return CONVROT_ERR_ALIGN;
+    if (workspace_bytes < convrot_workspace_bytes8(M, K)) return CONVROT_ERR_WORKSPACE;
+
+    uint8_t *xq = static_cast<uint8_t *>(workspace);
+    float *xs = reinterpret_cast<float *>(xq + round_up((size_t)M * (size_t)K, 256));
+    hipStream_t s = (hipStream_t)stream;
+    if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, 8, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
+    return from_hip(convrot::launch_gemm_w8a8(xq, xs, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr, s));
 }
 
 }  // extern "C"

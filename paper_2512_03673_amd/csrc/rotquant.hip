@@ -100,7 +100,8 @@ constexpr float group_norm() { return G == 4 ? 0.5f : G == 16 ? 0.25f : G == 64 
 }  // namespace
 
 // grid.x = ceil(rows / rows_per_block); block = rows_per_block * T threads, T = 64 * waves_per_row.
-template <int G, int U, int BLOCK>
+// BITS = 4: two codes per byte, [-7, 7]; BITS = 8 (the W8A8 variant of the layer): one int8 per code, [-127, 127].
+template <int G, int U, int BLOCK, int BITS>
 __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
                                                          int T, uint8_t *__restrict__ Xq,
                                                          float *__restrict__ scale)
@@ -162,7 +163,8 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
 
     const float norm = group_norm<G>();
     const float a = amax * norm;                       // exact: power-of-two scaling
-    const float s = (a == 0.0f) ? 1.0f : a / 7.0f;     // IEEE division
+    constexpr float kQmax = BITS == 4 ? 7.0f : 127.0f;
+    const float s = (a == 0.0f) ? 1.0f : a / kQmax;    // IEEE division
     const float r = norm / s;                          // IEEE division
     if (row_ok && t == 0) scale[row] = s;
 
@@ -176,8 +178,17 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
     // scale is a short dyadic number) redoes its codes through the exact residual
     // e = z - q su (one rounding of a quantity that is representable whenever q is the nearest or
     // a neighbouring integer), which decides the rounding, ties to even, without a division.
-    constexpr float kMagic = 12582912.0f + 8.0f;
-    constexpr uint32_t kMagicBits = 0x4B400008u;
+    // (BITS = 8: the same with q + 128 in the low byte, four codes per dword, Horner in base 256.)
+    constexpr uint32_t kOff = BITS == 4 ? 8u : 128u;          // offset that keeps every digit positive
+    constexpr int kDigit = BITS;                               // bits per code
+    constexpr int kPerDword = 32 / BITS;
+    constexpr int kDwords = kUnit / kPerDword;                 // output dwords per unit: 2 or 4
+    constexpr float kMagic = 12582912.0f + (float)kOff;
+    constexpr uint32_t kC = 0x4B400000u;                       // bits of 1.5 * 2^23
+    constexpr uint32_t kFlip = BITS == 4 ? 0x88888888u : 0x80808080u;   // offset-binary digits -> two's complement
+    constexpr uint32_t kDigitMask = (1u << BITS) - 1u;
+    // sum_e C 2^(BITS e) mod 2^32: only the first terms survive
+    constexpr uint32_t kBias = BITS == 4 ? kC + (kC << 4) + (kC << 8) : kC + (kC << 8);
     const float su = s / norm;                                      // scale in un-normalised units (exact)
     const float r_lo = r * (1.0f - 0x1p-21f), r_hi = r * (1.0f + 0x1p-21f);
     const float half_su = 0.5f * su;
@@ -185,55 +196,56 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
 #pragma unroll
     for (int i = 0; i < U; ++i) {
         uint32_t disagree = 0;
-        uint32_t code[2];
+        uint32_t code[kDwords];
 #pragma unroll
-        for (int hlf = 0; hlf < 2; ++hlf) {
-            // Horner in base 16 over the raw float bits: sum_e (C + u_e) 16^e mod 2^32, C the magic's bits
+        for (int w = 0; w < kDwords; ++w) {
+            // Horner over the raw float bits: sum_e (C + u_e) 2^(BITS e) mod 2^32, C the magic's bits
             // (the same sum over the other bracket: digits differ by at most one, so the two sums are
             // equal exactly when every pair of codes is)
             uint32_t acc = 0, acc_hi = 0;
 #pragma unroll
-            for (int e = 7; e >= 0; --e) {
-                const float z = v[i][8 * hlf + e];
-                acc = (acc << 4) + __float_as_uint(fmaf(z, r_lo, kMagic));
-                acc_hi = (acc_hi << 4) + __float_as_uint(fmaf(z, r_hi, kMagic));
+            for (int e = kPerDword - 1; e >= 0; --e) {
+                const float z = v[i][kPerDword * w + e];
+                acc = (acc << kDigit) + __float_as_uint(fmaf(z, r_lo, kMagic));
+                acc_hi = (acc_hi << kDigit) + __float_as_uint(fmaf(z, r_hi, kMagic));
             }
             disagree |= acc ^ acc_hi;
-            // remove sum_e (C - 8) 16^e (only e = 0, 1, 2 survive mod 2^32), then offset-binary
-            // nibbles -> two's complement
-            constexpr uint32_t kBias = (kMagicBits - 8u) + ((kMagicBits - 8u) << 4) + ((kMagicBits - 8u) << 8);
-            code[hlf] = (acc - kBias) ^ 0x88888888u;
+            code[w] = (acc - kBias) ^ kFlip;
         }
         if (__builtin_amdgcn_ballot_w64(disagree != 0) != 0) {   // wavefront-uniform, rare
 #pragma unroll
-            for (int hlf = 0; hlf < 2; ++hlf) {
+            for (int w = 0; w < kDwords; ++w) {
                 uint32_t d = 0;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float z = v[i][8 * hlf + e];
+                for (int e = 0; e < kPerDword; ++e) {
+                    const float z = v[i][kPerDword * w + e];
                     float q = rintf(z * r);
                     const float res = fmaf(-q, su, z);
                     const bool odd = ((int)q & 1) != 0;
                     const bool up = res > half_su || (res == half_su && odd);
                     const bool dn = res < -half_su || (res == -half_su && odd);
                     q += (up ? 1.0f : 0.0f) - (dn ? 1.0f : 0.0f);
-                    d |= ((uint32_t)(int)q & 0xFu) << (4 * e);
+                    d |= ((uint32_t)(int)q & kDigitMask) << (kDigit * e);
                 }
-                code[hlf] = d;
+                code[w] = d;
             }
         }
-        const uint32_t d0 = code[0], d1 = code[1];
         const int unit = i * T + tf;
         if (row_ok && unit < units) {
-            u32x2 *o = reinterpret_cast<u32x2 *>(Xq + row * (int64_t)(K / 2) + (int64_t)unit * (kUnit / 2));
-            __builtin_nontemporal_store(u32x2{d0, d1}, o);
+            if constexpr (BITS == 4) {
+                u32x2 *o = reinterpret_cast<u32x2 *>(Xq + row * (int64_t)(K / 2) + (int64_t)unit * (kUnit / 2));
+                __builtin_nontemporal_store(u32x2{code[0], code[1]}, o);
+            } else {
+                u32x4 *o = reinterpret_cast<u32x4 *>(Xq + row * (int64_t)K + (int64_t)unit * kUnit);
+                __builtin_nontemporal_store(u32x4{code[0], code[1], code[2], code[3]}, o);
+            }
         }
     }
 }
 
 namespace {
 
-template <int G, int U>
+template <int G, int U, int BITS>
 hipError_t launch_gu(const void *X, int64_t rows, int K, int waves_per_row, void *Xq, float *scale,
                      hipStream_t stream)
 {
@@ -241,19 +253,19 @@ hipError_t launch_gu(const void *X, int64_t rows, int K, int waves_per_row, void
     if (T <= 256) {
         const int rpb = 256 / T;
         const unsigned grid = (unsigned)((rows + rpb - 1) / rpb);
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 256>), dim3(grid), dim3(256), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 256, BITS>), dim3(grid), dim3(256), 0, stream,
                            (const uint16_t *)X, rows, K, T, (uint8_t *)Xq, scale);
     } else if (T <= 512) {
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 512>), dim3((unsigned)rows), dim3(512), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 512, BITS>), dim3((unsigned)rows), dim3(512), 0, stream,
                            (const uint16_t *)X, rows, K, 512, (uint8_t *)Xq, scale);
     } else {
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 1024>), dim3((unsigned)rows), dim3(1024), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 1024, BITS>), dim3((unsigned)rows), dim3(1024), 0, stream,
                            (const uint16_t *)X, rows, K, 1024, (uint8_t *)Xq, scale);
     }
     return hipGetLastError();
 }
 
-template <int G>
+template <int G, int BITS>
 hipError_t launch_g(const void *X, int64_t rows, int K, void *Xq, float *scale, hipStream_t stream)
 {
     // Pick the wavefronts per row (1, 2, 4, 8 or 16) so that every lane holds at most 4 units,
@@ -263,27 +275,35 @@ hipError_t launch_g(const void *X, int64_t rows, int K, void *Xq, float *scale, 
     while (wv < 16 && (chunks + wv - 1) / wv > 4) wv *= 2;
     const int u = (chunks + wv - 1) / wv;
     switch (u) {
-        case 1: return launch_gu<G, 1>(X, rows, K, wv, Xq, scale, stream);
-        case 2: return launch_gu<G, 2>(X, rows, K, wv, Xq, scale, stream);
-        case 3: return launch_gu<G, 3>(X, rows, K, wv, Xq, scale, stream);
-        default: return launch_gu<G, 4>(X, rows, K, wv, Xq, scale, stream);
+        case 1: return launch_gu<G, 1, BITS>(X, rows, K, wv, Xq, scale, stream);
+        case 2: return launch_gu<G, 2, BITS>(X, rows, K, wv, Xq, scale, stream);
+        case 3: return launch_gu<G, 3, BITS>(X, rows, K, wv, Xq, scale, stream);
+        default: return launch_gu<G, 4, BITS>(X, rows, K, wv, Xq, scale, stream);
+    }
+}
+
+template <int BITS>
+hipError_t launch_bits(const void *X, int64_t rows, int64_t K, int group, void *Xq, float *scale, hipStream_t stream)
+{
+    switch (group) {
+        case 4: return launch_g<4, BITS>(X, rows, (int)K, Xq, scale, stream);
+        case 16: return launch_g<16, BITS>(X, rows, (int)K, Xq, scale, stream);
+        case 64: return launch_g<64, BITS>(X, rows, (int)K, Xq, scale, stream);
+        case 256: return launch_g<256, BITS>(X, rows, (int)K, Xq, scale, stream);
+        case 1024: return launch_g<1024, BITS>(X, rows, (int)K, Xq, scale, stream);
+        default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, void *Xq, float *scale,
+hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, int bits, void *Xq, float *scale,
                            hipStream_t stream)
 {
     if (rows == 0) return hipSuccess;
-    switch (group) {
-        case 4: return launch_g<4>(X, rows, (int)K, Xq, scale, stream);
-        case 16: return launch_g<16>(X, rows, (int)K, Xq, scale, stream);
-        case 64: return launch_g<64>(X, rows, (int)K, Xq, scale, stream);
-        case 256: return launch_g<256>(X, rows, (int)K, Xq, scale, stream);
-        case 1024: return launch_g<1024>(X, rows, (int)K, Xq, scale, stream);
-        default: return hipErrorInvalidValue;
-    }
+    if (bits == 4) return launch_bits<4>(X, rows, K, group, Xq, scale, stream);
+    if (bits == 8) return launch_bits<8>(X, rows, K, group, Xq, scale, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace convrot

@@ -22,13 +22,13 @@ def lib():
 def declared_symbols():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(conv(?:rot|linear4bit)_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(conv(?:rot|linear4bit|linear8bit)_\w+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(lib):
     from paper_2512_03673_amd import binding
     names = declared_symbols()
-    assert len(names) == 9
+    assert len(names) == 15
     assert sorted(binding.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -43,6 +43,7 @@ def test_size_queries_and_strings(lib):
     assert b.workspace_bytes(4608, 3072) == 4608 * 1536 + 4608 * 4
     assert b.workspace_bytes(3, 32) == 256 + 256
     assert b.workspace_bytes(0, 32) == 0
+    assert b.workspace_bytes8(4608, 3072) == 4608 * 3072 + 4608 * 4
     assert b.status_string(0) == "ok"
     assert "group" in b.status_string(-3)
     assert b.status_string(-99) == "unknown status"
@@ -83,6 +84,17 @@ def test_argument_validation_without_a_device(lib):
     assert fw(A, A, A, A, 4, 4, 1024, 16, A, A + 16, 1 << 20, None) == -4
     assert fw(A, A, A, A + 1, 4, 4, 1024, 16, A, A, 1 << 20, None) == -4
     assert fw(A, A, A, None, 4, 4, 1024, 16, A, A, 100, None) == -5
+    # W8A8 variant: same validation, K % 64 == 0 in addition
+    f8, g8, fw8 = lib.convrot_rotquant_act8, lib.convrot_w8a8_gemm_dequant, lib.convlinear8bit_forward
+    assert f8(A, 4, 96, 16, A, A, None) == -2            # K % 64 != 0
+    assert f8(None, 4, 1024, 16, A, A, None) == -1
+    assert lib.convrot_prepare_weight8(A, 4, 1024, 5, A, A, None) == -3
+    assert g8(A, A, A, A, None, 4, 4, 96, A, None) == -2
+    assert g8(A, None, A, A, None, 4, 4, 1024, A, None) == -1
+    assert lib.convrot_w8a8_gemm_i32(A, A, 4, 4, 1024, None, None) == -1
+    assert fw8(A, A, A, None, 4, 4, 1024, 16, A, A, 100, None) == -5
+    assert fw8(A, A, A, None, 4, 4, 1056, 16, A, A, 1 << 20, None) == -2
+    assert g8(A, A, A, A, None, 0, 4, 1024, A, None) == 0
     # empty problems are valid no-ops and launch nothing
     assert f(A, 0, 1024, 16, A, A, None) == 0
     assert g(A, A, A, A, None, 0, 4, 1024, A, None) == 0
