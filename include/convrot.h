@@ -130,6 +130,24 @@ int convrot_w4a4_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, 
                           int32_t *acc, void *stream);
 
 /*
+ * Diagnostic, not a hot-path call: the paper's outlier-amplitude metric max |X H| (Sec. 4.2; Table 5-1
+ * and Fig. 3-2 report it on FLUX activations), per row, for three choices of the group-wise rotation:
+ *   kind 0 (CONVROT_ROT_NONE)      no rotation: max_k |X[m,k]|
+ *   kind 1 (CONVROT_ROT_REGULAR)   the layer's regular Hadamard rotation: max_k |R_g(X)[m,k]| (= 7 x_scale[m])
+ *   kind 2 (CONVROT_ROT_SYLVESTER) the Sylvester Hadamard matrix of order g instead, normalised alike -
+ *                                  the comparison the paper draws (its first column of ones adds up a
+ *                                  one-signed row: Sec. 3.2)
+ *   X_bf16      DEVICE in   [M, K] bf16
+ *   row_absmax  DEVICE out  [M] fp32
+ * CONVROT_ERR_GROUP for a `kind` outside 0..2 as for a bad `group`.
+ */
+#define CONVROT_ROT_NONE 0
+#define CONVROT_ROT_REGULAR 1
+#define CONVROT_ROT_SYLVESTER 2
+int convrot_rotated_absmax(const void *X_bf16, int64_t M, int64_t K, int group, int kind,
+                           float *row_absmax, void *stream);
+
+/*
  * ---- W8A8 variant of the layer (the paper's W8A8 rows, Sec. 5, Tables 5-2 and 5-4, and the ~20 % of
  * layers its mixed-precision mode keeps at 8 bits): the same rotation, the same symmetric quantiser
  * with 127 levels (s = a / 127, q in [-127, 127]), int8 codes stored one per byte, row-major [rows, K].

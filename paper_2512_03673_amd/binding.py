@@ -23,7 +23,8 @@ EXPORTS = ("convrot_status_string", "convrot_version", "convrot_packed_bytes", "
            "convrot_prepare_weight", "convrot_rotquant_act", "convrot_w4a4_gemm_dequant",
            "convlinear4bit_forward", "convrot_w4a4_gemm_i32",
            "convrot_prepare_weight8", "convrot_rotquant_act8", "convrot_w8a8_gemm_dequant",
-           "convlinear8bit_forward", "convrot_w8a8_gemm_i32", "convrot_workspace_bytes8")
+           "convlinear8bit_forward", "convrot_w8a8_gemm_i32", "convrot_rotated_absmax",
+           "convrot_workspace_bytes8")
 
 _lib = None
 
@@ -65,6 +66,7 @@ def load() -> ctypes.CDLL:
     lib.convrot_w8a8_gemm_dequant.argtypes = lib.convrot_w4a4_gemm_dequant.argtypes
     lib.convlinear8bit_forward.argtypes = lib.convlinear4bit_forward.argtypes
     lib.convrot_w8a8_gemm_i32.argtypes = lib.convrot_w4a4_gemm_i32.argtypes
+    lib.convrot_rotated_absmax.argtypes = [vp, i64, i64, i32, i32, vp, vp]
     for name in EXPORTS[4:-1]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -189,6 +191,20 @@ def convlinear4bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Ten
                                          _ptr(workspace), workspace.numel(), _stream(stream)),
            "convlinear4bit_forward")
     return Y
+
+
+ROT_NONE, ROT_REGULAR, ROT_SYLVESTER = 0, 1, 2
+
+
+def convrot_rotated_absmax(X: torch.Tensor, group: int, kind: int, out: Optional[torch.Tensor] = None,
+                           stream=None) -> torch.Tensor:
+    """Per-row max |R(X)| for kind ROT_NONE / ROT_REGULAR / ROT_SYLVESTER (diagnostic) -> f32 [M]."""
+    _dev(X, torch.bfloat16, "X")
+    M, K = X.shape
+    out = torch.empty((M,), dtype=torch.float32, device=X.device) if out is None else out
+    _check(load().convrot_rotated_absmax(_ptr(X), M, K, group, kind, _ptr(out), _stream(stream)),
+           "convrot_rotated_absmax")
+    return out
 
 
 # ---------------------------------------------------------------------------- W8A8 variant

@@ -126,6 +126,19 @@ int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
     return from_hip(convrot::launch_gemm_w4a4(xq, xs, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr, s));
 }
 
+int convrot_rotated_absmax(const void *X_bf16, int64_t M, int64_t K, int group, int kind, float *row_absmax,
+                           void *stream)
+{
+    if (int rc = check_group(group)) return rc;
+    if (kind < 0 || kind > 2) return CONVROT_ERR_GROUP;
+    if (M < 0 || M > INT32_MAX) return CONVROT_ERR_SHAPE;
+    if (int rc = check_k(K)) return rc;
+    if (K % group != 0) return CONVROT_ERR_SHAPE;
+    if (missing(X_bf16, M) || missing(row_absmax, M)) return CONVROT_ERR_NULL;
+    if (!aligned(X_bf16, 16) || !aligned(row_absmax, 4)) return CONVROT_ERR_ALIGN;
+    return from_hip(convrot::launch_rotated_absmax(X_bf16, M, K, group, kind, row_absmax, (hipStream_t)stream));
+}
+
 // ---- W8A8 variant
 
 size_t convrot_workspace_bytes8(int64_t M, int64_t K)

@@ -11,6 +11,10 @@ namespace convrot {
 hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, int bits, void *Xq, float *scale,
                            hipStream_t stream);
 
+// Per-row max |R(X)| for kind 0 = no rotation, 1 = the regular Hadamard rotation, 2 = Sylvester (diagnostic).
+hipError_t launch_rotated_absmax(const void *X, int64_t rows, int64_t K, int group, int kind, float *out,
+                                 hipStream_t stream);
+
 // W4A4 GEMM on packed codes.  Exactly one of Y_bf16 / acc_i32 is non-null:
 //   Y_bf16 : dequantised bf16 output (needs x_scale, w_scale; bias_bf16 [N] or null)
 //   acc_i32: raw int32 accumulators

@@ -245,6 +245,74 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
 
 namespace {
 
+// Sylvester (Walsh) Hadamard matrix of order G on a unit: radix-2 butterflies (a, b) -> (a + b, a - b),
+// in-group index bits 0-3 inside the lane's 16 elements, the higher ones across lanes.
+template <int G>
+__device__ __forceinline__ void sylvester_unit(float (&v)[kUnit], int lane)
+{
+    constexpr int kBitsInUnit = G >= 16 ? 4 : 2;
+#pragma unroll
+    for (int b = 0; b < kBitsInUnit; ++b)
+#pragma unroll
+        for (int e = 0; e < kUnit; ++e)
+            if (!(e & (1 << b))) {
+                const float lo = v[e], hi = v[e | (1 << b)];
+                v[e] = lo + hi;
+                v[e | (1 << b)] = lo - hi;
+            }
+    constexpr int kLaneBits = G == 64 ? 2 : G == 256 ? 4 : G == 1024 ? 6 : 0;
+#pragma unroll
+    for (int b = 0; b < kLaneBits; ++b) {
+        const bool upper = (lane >> b) & 1;
+#pragma unroll
+        for (int e = 0; e < kUnit; ++e) {
+            const float other = __shfl_xor(v[e], 1 << b, 64);
+            v[e] = upper ? other - v[e] : v[e] + other;
+        }
+    }
+}
+
+}  // namespace
+
+// Diagnostic (the paper's outlier-amplitude metric max |X H|, Sec. 4.2 and Table 5-1): per-row maximum of
+// the rotated activations for KIND 0 = no rotation, 1 = the layer's regular Hadamard rotation, 2 = the
+// Sylvester Hadamard matrix of the same order.  One wavefront per row, 1024 elements per pass.
+template <int G, int KIND>
+__global__ __launch_bounds__(256) void rotated_absmax_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
+                                                             float *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;                     // wavefront-uniform
+    const int units = K / kUnit;
+    const uint16_t *xrow = X + row * (int64_t)K;
+    float amax = 0.0f;
+    for (int base = 0; base < units; base += 64) {
+        const int unit = base + lane;
+        const bool ok = unit < units;            // K % g == 0: a rotation group is all-valid or all-invalid
+        const u32x4 *p = reinterpret_cast<const u32x4 *>(xrow + (int64_t)(ok ? unit : units - 1) * kUnit);
+        const u32x4 lo = p[0], hi = p[1];
+        const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        float v[kUnit];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            v[2 * j] = __uint_as_float(w[j] << 16);
+            v[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+        }
+        if constexpr (KIND == 1) rotate_unit<G>(v);
+        if constexpr (KIND == 2) sylvester_unit<G>(v, lane);
+        float m = 0.0f;
+#pragma unroll
+        for (int e = 0; e < kUnit; ++e) m = fmaxf(m, fabsf(v[e]));
+        amax = ok ? fmaxf(amax, m) : amax;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
+    if (lane == 0) out[row] = KIND == 0 ? amax : amax * group_norm<G>();
+}
+
+namespace {
+
 template <int G, int U, int BITS>
 hipError_t launch_gu(const void *X, int64_t rows, int K, int waves_per_row, void *Xq, float *scale,
                      hipStream_t stream)
@@ -304,6 +372,36 @@ hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, in
     if (bits == 4) return launch_bits<4>(X, rows, K, group, Xq, scale, stream);
     if (bits == 8) return launch_bits<8>(X, rows, K, group, Xq, scale, stream);
     return hipErrorInvalidValue;
+}
+
+namespace {
+
+template <int G>
+hipError_t launch_absmax_g(const void *X, int64_t rows, int K, int kind, float *out, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    const uint16_t *x = (const uint16_t *)X;
+    if (kind == 0) hipLaunchKernelGGL((rotated_absmax_kernel<G, 0>), grid, block, 0, stream, x, rows, K, out);
+    else if (kind == 1) hipLaunchKernelGGL((rotated_absmax_kernel<G, 1>), grid, block, 0, stream, x, rows, K, out);
+    else hipLaunchKernelGGL((rotated_absmax_kernel<G, 2>), grid, block, 0, stream, x, rows, K, out);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_rotated_absmax(const void *X, int64_t rows, int64_t K, int group, int kind, float *out,
+                                 hipStream_t stream)
+{
+    if (rows == 0) return hipSuccess;
+    if (kind < 0 || kind > 2) return hipErrorInvalidValue;
+    switch (group) {
+        case 4: return launch_absmax_g<4>(X, rows, (int)K, kind, out, stream);
+        case 16: return launch_absmax_g<16>(X, rows, (int)K, kind, out, stream);
+        case 64: return launch_absmax_g<64>(X, rows, (int)K, kind, out, stream);
+        case 256: return launch_absmax_g<256>(X, rows, (int)K, kind, out, stream);
+        case 1024: return launch_absmax_g<1024>(X, rows, (int)K, kind, out, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace convrot

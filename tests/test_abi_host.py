@@ -28,7 +28,7 @@ def declared_symbols():
 def test_header_symbols_are_exported(lib):
     from paper_2512_03673_amd import binding
     names = declared_symbols()
-    assert len(names) == 15
+    assert len(names) == 16
     assert sorted(binding.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -95,6 +95,10 @@ def test_argument_validation_without_a_device(lib):
     assert fw8(A, A, A, None, 4, 4, 1024, 16, A, A, 100, None) == -5
     assert fw8(A, A, A, None, 4, 4, 1056, 16, A, A, 1 << 20, None) == -2
     assert g8(A, A, A, A, None, 0, 4, 1024, A, None) == 0
+    d = lib.convrot_rotated_absmax
+    assert d(A, 4, 1024, 16, 3, A, None) == -3 and d(A, 4, 1024, 8, 1, A, None) == -3
+    assert d(None, 4, 1024, 16, 1, A, None) == -1 and d(A, 4, 1000, 16, 1, A, None) == -2
+    assert d(A, 0, 1024, 16, 2, A, None) == 0
     # empty problems are valid no-ops and launch nothing
     assert f(A, 0, 1024, 16, A, A, None) == 0
     assert g(A, A, A, A, None, 0, 4, 1024, A, None) == 0
