@@ -85,7 +85,7 @@ def test_prepare_weight_is_the_same_operation(cr):
 
 # ------------------------------------------------------------------ kernel B: integer GEMM
 @pytest.mark.parametrize("M,N,K", [(256, 256, 128), (300, 520, 1024), (1, 1, 32), (33, 7, 96), (257, 513, 3072),
-                                   (64, 1030, 12288), (513, 258, 160)])
+                                   (64, 1030, 12288), (513, 258, 160), (40, 136, 65536), (3, 2, 65504)])
 def test_gemm_i32_bit_exact(cr, M, N, K):
     rng = np.random.default_rng(M * 7 + N * 3 + K)
     qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)

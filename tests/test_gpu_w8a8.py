@@ -60,7 +60,7 @@ def test_rotquant8_closed_forms(cr):
 
 
 @pytest.mark.parametrize("M,N,K", [(256, 128, 64), (300, 520, 1024), (1, 1, 64), (33, 7, 192), (257, 513, 3072),
-                                   (64, 1030, 12288), (513, 258, 128)])
+                                   (64, 1030, 12288), (513, 258, 128), (40, 136, 65536)])
 def test_gemm8_i32_bit_exact(cr, M, N, K):
     rng = np.random.default_rng(M * 5 + N * 3 + K)
     qx = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
