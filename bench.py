@@ -88,7 +88,7 @@ def measure_layer(spec, cr, wl, torch, np, steps: int, warmup: int):
     Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     ws = torch.empty((cr.workspace_bytes(M, K),), dtype=torch.uint8, device="cuda")
     fns = {"forward": lambda: cr.convlinear4bit_forward(X, Wq, Ws, g, Y, ws),
-           "gemm": lambda: cr.convrot_w4a4_gemm_dequant(Xq, Xs, Wq, Ws, Y),
+           "gemm": lambda: cr.convrot_w4a4_gemm_dequant(Xq, Xs, Wq, Ws, K, Y),
            "rotquant": lambda: cr.convrot_rotquant_act(X, g, Xq, Xs),
            "prepare_weight": lambda: cr.convrot_prepare_weight(W, g, Wq, Ws)}
     for _ in range(warmup):
@@ -146,7 +146,7 @@ def main() -> int:
     del W
     Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     ws = torch.empty((cr.workspace_bytes(M, K),), dtype=torch.uint8, device="cuda")
-    Xq = torch.empty((M, K // 2), dtype=torch.uint8, device="cuda")
+    Xq = torch.empty((cr.packed_bytes(M, K),), dtype=torch.uint8, device="cuda")
     Xs = torch.empty((M,), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
@@ -166,7 +166,7 @@ def main() -> int:
         cr.convrot_rotquant_act(X, g, Xq, Xs)
 
     def kern_b():
-        cr.convrot_w4a4_gemm_dequant(Xq, Xs, Wq, Ws, Y)
+        cr.convrot_w4a4_gemm_dequant(Xq, Xs, Wq, Ws, K, Y)
 
     for _ in range(max(5, args.warmup // 4)):
         kern_a(); kern_b()

@@ -27,11 +27,25 @@
  *   - Shapes: M, N >= 0 (M == 0 or N == 0 is a valid no-op, and a matrix with no rows may be
  *     passed as NULL), 0 < K <= CONVROT_MAX_K,
  *     K % 32 == 0 and K % g == 0 (the paper defines no padding for a ragged last block).
- *     Data pointers must be 16-byte aligned, scale pointers 4-byte aligned.
+ *     bf16 and int32 matrices must be 16-byte aligned, code matrices 256-byte aligned, scale
+ *     pointers 4-byte aligned.
  *
- * Packed 4-bit layout ("canonical", shared by activations and weights): a row of K codes is
- * K/2 bytes; byte j holds code 2j in bits 0-3 and code 2j+1 in bits 4-7, each a 4-bit two's
- * complement integer in [-7, 7] (-8 is never produced).
+ * Codes.  A 4-bit code is a two's complement integer in [-7, 7] (-8 is never produced); a row of K
+ * codes is K/2 bytes, byte j holding code 2j in bits 0-3 and code 2j+1 in bits 4-7.  (8-bit variant:
+ * one int8 in [-127, 127] per byte, K bytes per row.)
+ *
+ * Panel layout of a code matrix (shared by activations and weights, 4-bit and 8-bit).  The matrix
+ * of `rows` rows of B bytes (B = K/2, or K for 8-bit codes) is stored as 1 KB panels of 16 rows x
+ * 64 bytes, the K-panels of the same 16 rows adjacent:
+ *
+ *     byte b of row r  at  ((r / 16) * KP + b / 64) * 1024 + (r % 16) * 64 + b % 64,   KP = ceil(B / 64)
+ *
+ * so that the GEMM's loads (16 rows x 64 bytes of K at a time) are contiguous kilobytes.  A code
+ * matrix therefore occupies ceil(rows / 16) * KP * 1024 bytes (convrot_packed_bytes): bytes of the
+ * last K-panel past B are written as zero codes by the producing call, the rows past `rows` of the
+ * last row panel are never read or written (a caller that fills a code matrix itself must zero
+ * that K padding too).  The layout is a contract between the producing calls
+ * (convrot_prepare_weight, convrot_rotquant_act) and the GEMM calls of the same library version.
  *
  * Quantiser (both operands): a = max_k |x'[k]| over the rotated row, s = a / 7 in fp32 (s = 1
  * when a == 0), q = clamp(round_half_even(x' / s), -7, 7).
@@ -46,7 +60,7 @@
 extern "C" {
 #endif
 
-#define CONVROT_VERSION 200          /* major*10000 + minor*100 + patch */
+#define CONVROT_VERSION 300          /* major*10000 + minor*100 + patch */
 #define CONVROT_MAX_K 65536          /* longest row the single-pass rotate+quantise kernel holds on chip */
 
 typedef enum convrot_status {
@@ -65,18 +79,19 @@ const char *convrot_status_string(int status);
 /* Host.  CONVROT_VERSION of the loaded library. */
 int convrot_version(void);
 
-/* Host.  Bytes of a packed code matrix with `rows` rows of K codes: rows * K / 2.  0 on bad input. */
+/* Host.  Bytes of a 4-bit code matrix with `rows` rows of K codes in the panel layout
+ * (ceil(rows / 16) * ceil(K / 128) KB).  0 on bad input. */
 size_t convrot_packed_bytes(int64_t rows, int64_t K);
 
-/* Host.  Bytes of workspace convlinear4bit_forward needs for an [M, K] activation: the packed
- * codes (rounded up to 256 bytes) followed by M fp32 scales (rounded up to 256).  0 on bad input. */
+/* Host.  Bytes of workspace convlinear4bit_forward needs for an [M, K] activation: the code matrix
+ * (convrot_packed_bytes(M, K)) followed by M fp32 scales (rounded up to 256).  0 on bad input. */
 size_t convrot_workspace_bytes(int64_t M, int64_t K);
 
 /*
  * Offline weight preparation (Eq. 12-13, Sec. 5.2 "per-channel"): W' = R_g(W); for each output
  * channel n, s_w[n] = max_k |W'[n,k]| / 7 and q_w[n,:] = Q4(W'[n,:]); packed.
  *   W_bf16   DEVICE in   [N, K] bf16
- *   Wq       DEVICE out  [N, K/2] bytes, canonical packed layout
+ *   Wq       DEVICE out  convrot_packed_bytes(N, K) bytes: 4-bit codes [N, K], panel layout
  *   w_scale  DEVICE out  [N] fp32
  */
 int convrot_prepare_weight(const void *W_bf16, int64_t N, int64_t K, int group,
@@ -86,7 +101,7 @@ int convrot_prepare_weight(const void *W_bf16, int64_t N, int64_t K, int group,
  * Online activation path (Sec. 4.2 + Eq. 1, Sec. 5.2 "per-token"): X' = R_g(X), per-token scale,
  * 4-bit codes, packed - one pass over X.
  *   X_bf16   DEVICE in   [M, K] bf16
- *   Xq       DEVICE out  [M, K/2] bytes, canonical packed layout
+ *   Xq       DEVICE out  convrot_packed_bytes(M, K) bytes: 4-bit codes [M, K], panel layout
  *   x_scale  DEVICE out  [M] fp32
  */
 int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group,
@@ -95,7 +110,7 @@ int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group,
 /*
  * W4A4 GEMM with the dequantisation fused (Sec. 4.3; suppl. Sec. B lists them as two stages):
  * Y[m,n] = bf16( (sum_k q_x[m,k] q_w[n,k]) * x_scale[m] * w_scale[n] + bias[n] ).
- *   Xq, Wq            DEVICE in   packed codes [M, K/2], [N, K/2]
+ *   Xq, Wq            DEVICE in   4-bit codes [M, K], [N, K], panel layout
  *   x_scale, w_scale  DEVICE in   [M], [N] fp32
  *   bias_bf16         DEVICE in   [N] bf16, or NULL for none.  Eq. 10 of the paper has no bias; the
  *                                 linear layers it replaces carry one, added here in fp32 before the
@@ -110,7 +125,7 @@ int convrot_w4a4_gemm_dequant(const void *Xq, const float *x_scale, const void *
  * The whole ConvLinear4bit forward (Sec. 4.3): convrot_rotquant_act into the workspace, then
  * convrot_w4a4_gemm_dequant, on one stream.
  *   X_bf16     DEVICE in   [M, K] bf16
- *   Wq         DEVICE in   [N, K/2] from convrot_prepare_weight (same `group`)
+ *   Wq         DEVICE in   codes [N, K] from convrot_prepare_weight (same `group`)
  *   w_scale    DEVICE in   [N]
  *   bias_bf16  DEVICE in   [N] bf16 or NULL, as above
  *   Y_bf16     DEVICE out  [M, N] bf16
@@ -150,21 +165,23 @@ int convrot_rotated_absmax(const void *X_bf16, int64_t M, int64_t K, int group, 
 /*
  * ---- W8A8 variant of the layer (the paper's W8A8 rows, Sec. 5, Tables 5-2 and 5-4, and the ~20 % of
  * layers its mixed-precision mode keeps at 8 bits): the same rotation, the same symmetric quantiser
- * with 127 levels (s = a / 127, q in [-127, 127]), int8 codes stored one per byte, row-major [rows, K].
- * Everything said above about pointers, streams, errors and shapes holds, with K % 64 == 0 in
- * addition (CONVROT_ERR_SHAPE otherwise).
+ * with 127 levels (s = a / 127, q in [-127, 127]), int8 codes stored one per byte in the panel layout.
+ * Everything said above about pointers, streams, errors and shapes holds.
  */
 
-/* Host.  Workspace of convlinear8bit_forward: int8 codes [M, K] (rounded up to 256 bytes) + M fp32 scales. */
+/* Host.  Bytes of an 8-bit code matrix [rows, K] in the panel layout (ceil(rows / 16) * ceil(K / 64) KB). */
+size_t convrot_packed_bytes8(int64_t rows, int64_t K);
+
+/* Host.  Workspace of convlinear8bit_forward: convrot_packed_bytes8(M, K) + M fp32 scales (rounded up to 256). */
 size_t convrot_workspace_bytes8(int64_t M, int64_t K);
 
-/* As convrot_prepare_weight / convrot_rotquant_act, 8-bit: Wq, Xq are [rows, K] int8. */
+/* As convrot_prepare_weight / convrot_rotquant_act, 8-bit: Wq, Xq are int8 codes [rows, K], panel layout. */
 int convrot_prepare_weight8(const void *W_bf16, int64_t N, int64_t K, int group,
                             void *Wq, float *w_scale, void *stream);
 int convrot_rotquant_act8(const void *X_bf16, int64_t M, int64_t K, int group,
                           void *Xq, float *x_scale, void *stream);
 
-/* As convrot_w4a4_gemm_dequant on int8 codes [M, K], [N, K]. */
+/* As convrot_w4a4_gemm_dequant on int8 codes [M, K], [N, K], panel layout. */
 int convrot_w8a8_gemm_dequant(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
                               const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16,
                               void *stream);

@@ -24,7 +24,7 @@ EXPORTS = ("convrot_status_string", "convrot_version", "convrot_packed_bytes", "
            "convlinear4bit_forward", "convrot_w4a4_gemm_i32",
            "convrot_prepare_weight8", "convrot_rotquant_act8", "convrot_w8a8_gemm_dequant",
            "convlinear8bit_forward", "convrot_w8a8_gemm_i32", "convrot_rotated_absmax",
-           "convrot_workspace_bytes8")
+           "convrot_workspace_bytes8", "convrot_packed_bytes8")
 
 _lib = None
 
@@ -67,7 +67,9 @@ def load() -> ctypes.CDLL:
     lib.convlinear8bit_forward.argtypes = lib.convlinear4bit_forward.argtypes
     lib.convrot_w8a8_gemm_i32.argtypes = lib.convrot_w4a4_gemm_i32.argtypes
     lib.convrot_rotated_absmax.argtypes = [vp, i64, i64, i32, i32, vp, vp]
-    for name in EXPORTS[4:-1]:
+    lib.convrot_packed_bytes8.argtypes = [i64, i64]
+    lib.convrot_packed_bytes8.restype = sz
+    for name in EXPORTS[4:-2]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -83,6 +85,10 @@ def version() -> int:
 
 def packed_bytes(rows: int, K: int) -> int:
     return int(load().convrot_packed_bytes(rows, K))
+
+
+def packed_bytes8(rows: int, K: int) -> int:
+    return int(load().convrot_packed_bytes8(rows, K))
 
 
 def workspace_bytes(M: int, K: int) -> int:
@@ -119,12 +125,24 @@ def _bias(b: Optional[torch.Tensor], N: int) -> None:
             raise ValueError("bias: need shape [N]")
 
 
+def _codes(t: torch.Tensor, nbytes: int, name: str) -> None:
+    """A code matrix is an opaque uint8 buffer in the library's panel layout."""
+    _dev(t, torch.uint8, name)
+    if t.numel() < nbytes:
+        raise ValueError(f"{name}: need {nbytes} bytes (convrot_packed_bytes), got {t.numel()}")
+
+
+def _new_codes(nbytes: int, device) -> torch.Tensor:
+    return torch.empty((nbytes,), dtype=torch.uint8, device=device)
+
+
 def convrot_prepare_weight(W: torch.Tensor, group: int, Wq: Optional[torch.Tensor] = None,
                            w_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """W bf16 [N, K] -> (Wq uint8 [N, K/2], w_scale f32 [N])."""
+    """W bf16 [N, K] -> (Wq uint8 [packed_bytes(N, K)], w_scale f32 [N])."""
     _dev(W, torch.bfloat16, "W")
     N, K = W.shape
-    Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device) if Wq is None else Wq
+    Wq = _new_codes(packed_bytes(N, K), W.device) if Wq is None else Wq
+    _codes(Wq, packed_bytes(N, K), "Wq")
     w_scale = torch.empty((N,), dtype=torch.float32, device=W.device) if w_scale is None else w_scale
     _check(load().convrot_prepare_weight(_ptr(W), N, K, group, _ptr(Wq), _ptr(w_scale), _stream(stream)),
            "convrot_prepare_weight")
@@ -133,10 +151,11 @@ def convrot_prepare_weight(W: torch.Tensor, group: int, Wq: Optional[torch.Tenso
 
 def convrot_rotquant_act(X: torch.Tensor, group: int, Xq: Optional[torch.Tensor] = None,
                          x_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """X bf16 [M, K] -> (Xq uint8 [M, K/2], x_scale f32 [M])."""
+    """X bf16 [M, K] -> (Xq uint8 [packed_bytes(M, K)], x_scale f32 [M])."""
     _dev(X, torch.bfloat16, "X")
     M, K = X.shape
-    Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=X.device) if Xq is None else Xq
+    Xq = _new_codes(packed_bytes(M, K), X.device) if Xq is None else Xq
+    _codes(Xq, packed_bytes(M, K), "Xq")
     x_scale = torch.empty((M,), dtype=torch.float32, device=X.device) if x_scale is None else x_scale
     _check(load().convrot_rotquant_act(_ptr(X), M, K, group, _ptr(Xq), _ptr(x_scale), _stream(stream)),
            "convrot_rotquant_act")
@@ -144,32 +163,25 @@ def convrot_rotquant_act(X: torch.Tensor, group: int, Xq: Optional[torch.Tensor]
 
 
 def convrot_w4a4_gemm_dequant(Xq: torch.Tensor, x_scale: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor,
-                              Y: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
+                              K: int, Y: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
                               stream=None) -> torch.Tensor:
-    """Packed codes + scales (+ bias bf16 [N]) -> Y bf16 [M, N]."""
-    _dev(Xq, torch.uint8, "Xq"); _dev(Wq, torch.uint8, "Wq")
+    """Code matrices + scales f32 [M], [N] (+ bias bf16 [N]) -> Y bf16 [M, N]."""
     _dev(x_scale, torch.float32, "x_scale"); _dev(w_scale, torch.float32, "w_scale")
-    M, Kb = Xq.shape
-    N, Kb2 = Wq.shape
-    if Kb != Kb2:
-        raise ValueError("K mismatch")
+    M, N = x_scale.shape[0], w_scale.shape[0]
+    _codes(Xq, packed_bytes(M, K), "Xq"); _codes(Wq, packed_bytes(N, K), "Wq")
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=Xq.device) if Y is None else Y
     _bias(bias, N)
     _check(load().convrot_w4a4_gemm_dequant(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N,
-                                            2 * Kb, _ptr(Y), _stream(stream)), "convrot_w4a4_gemm_dequant")
+                                            K, _ptr(Y), _stream(stream)), "convrot_w4a4_gemm_dequant")
     return Y
 
 
-def convrot_w4a4_gemm_i32(Xq: torch.Tensor, Wq: torch.Tensor, acc: Optional[torch.Tensor] = None,
-                          stream=None) -> torch.Tensor:
-    """Packed codes -> raw int32 accumulators [M, N] (gate / debug export)."""
-    _dev(Xq, torch.uint8, "Xq"); _dev(Wq, torch.uint8, "Wq")
-    M, Kb = Xq.shape
-    N, Kb2 = Wq.shape
-    if Kb != Kb2:
-        raise ValueError("K mismatch")
+def convrot_w4a4_gemm_i32(Xq: torch.Tensor, Wq: torch.Tensor, M: int, N: int, K: int,
+                          acc: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Code matrices of [M, K] and [N, K] -> raw int32 accumulators [M, N] (gate / debug export)."""
+    _codes(Xq, packed_bytes(M, K), "Xq"); _codes(Wq, packed_bytes(N, K), "Wq")
     acc = torch.empty((M, N), dtype=torch.int32, device=Xq.device) if acc is None else acc
-    _check(load().convrot_w4a4_gemm_i32(_ptr(Xq), _ptr(Wq), M, N, 2 * Kb, _ptr(acc), _stream(stream)),
+    _check(load().convrot_w4a4_gemm_i32(_ptr(Xq), _ptr(Wq), M, N, K, _ptr(acc), _stream(stream)),
            "convrot_w4a4_gemm_i32")
     return acc
 
@@ -178,11 +190,10 @@ def convlinear4bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Ten
                            Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                            bias: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """X bf16 [M, K], prepared weight -> Y bf16 [M, N]; `workspace` is a uint8 tensor of workspace_bytes(M, K)."""
-    _dev(X, torch.bfloat16, "X"); _dev(Wq, torch.uint8, "Wq"); _dev(w_scale, torch.float32, "w_scale")
+    _dev(X, torch.bfloat16, "X"); _dev(w_scale, torch.float32, "w_scale")
     M, K = X.shape
-    N = Wq.shape[0]
-    if Wq.shape[1] * 2 != K:
-        raise ValueError("K mismatch")
+    N = w_scale.shape[0]
+    _codes(Wq, packed_bytes(N, K), "Wq")
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if Y is None else Y
     if workspace is None:
         workspace = torch.empty((max(workspace_bytes(M, K), 256),), dtype=torch.uint8, device=X.device)
@@ -211,7 +222,8 @@ def convrot_rotated_absmax(X: torch.Tensor, group: int, kind: int, out: Optional
 def _rotquant8(fn_name: str, X: torch.Tensor, group: int, Xq, x_scale, stream):
     _dev(X, torch.bfloat16, "input")
     rows, K = X.shape
-    Xq = torch.empty((rows, K), dtype=torch.int8, device=X.device) if Xq is None else Xq
+    Xq = _new_codes(packed_bytes8(rows, K), X.device) if Xq is None else Xq
+    _codes(Xq, packed_bytes8(rows, K), "codes")
     x_scale = torch.empty((rows,), dtype=torch.float32, device=X.device) if x_scale is None else x_scale
     _check(getattr(load(), fn_name)(_ptr(X), rows, K, group, _ptr(Xq), _ptr(x_scale), _stream(stream)), fn_name)
     return Xq, x_scale
@@ -219,26 +231,23 @@ def _rotquant8(fn_name: str, X: torch.Tensor, group: int, Xq, x_scale, stream):
 
 def convrot_prepare_weight8(W: torch.Tensor, group: int, Wq: Optional[torch.Tensor] = None,
                             w_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """W bf16 [N, K] -> (Wq int8 [N, K], w_scale f32 [N])."""
+    """W bf16 [N, K] -> (Wq uint8 [packed_bytes8(N, K)], w_scale f32 [N])."""
     return _rotquant8("convrot_prepare_weight8", W, group, Wq, w_scale, stream)
 
 
 def convrot_rotquant_act8(X: torch.Tensor, group: int, Xq: Optional[torch.Tensor] = None,
                           x_scale: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """X bf16 [M, K] -> (Xq int8 [M, K], x_scale f32 [M])."""
+    """X bf16 [M, K] -> (Xq uint8 [packed_bytes8(M, K)], x_scale f32 [M])."""
     return _rotquant8("convrot_rotquant_act8", X, group, Xq, x_scale, stream)
 
 
 def convrot_w8a8_gemm_dequant(Xq: torch.Tensor, x_scale: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor,
-                              Y: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
+                              K: int, Y: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,
                               stream=None) -> torch.Tensor:
-    """int8 codes + scales (+ bias bf16 [N]) -> Y bf16 [M, N]."""
-    _dev(Xq, torch.int8, "Xq"); _dev(Wq, torch.int8, "Wq")
+    """8-bit code matrices + scales f32 [M], [N] (+ bias bf16 [N]) -> Y bf16 [M, N]."""
     _dev(x_scale, torch.float32, "x_scale"); _dev(w_scale, torch.float32, "w_scale")
-    M, K = Xq.shape
-    N, K2 = Wq.shape
-    if K != K2:
-        raise ValueError("K mismatch")
+    M, N = x_scale.shape[0], w_scale.shape[0]
+    _codes(Xq, packed_bytes8(M, K), "Xq"); _codes(Wq, packed_bytes8(N, K), "Wq")
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=Xq.device) if Y is None else Y
     _bias(bias, N)
     _check(load().convrot_w8a8_gemm_dequant(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K,
@@ -246,14 +255,10 @@ def convrot_w8a8_gemm_dequant(Xq: torch.Tensor, x_scale: torch.Tensor, Wq: torch
     return Y
 
 
-def convrot_w8a8_gemm_i32(Xq: torch.Tensor, Wq: torch.Tensor, acc: Optional[torch.Tensor] = None,
-                          stream=None) -> torch.Tensor:
-    """int8 codes -> raw int32 accumulators [M, N] (gate / debug export)."""
-    _dev(Xq, torch.int8, "Xq"); _dev(Wq, torch.int8, "Wq")
-    M, K = Xq.shape
-    N, K2 = Wq.shape
-    if K != K2:
-        raise ValueError("K mismatch")
+def convrot_w8a8_gemm_i32(Xq: torch.Tensor, Wq: torch.Tensor, M: int, N: int, K: int,
+                          acc: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """8-bit code matrices of [M, K] and [N, K] -> raw int32 accumulators [M, N] (gate / debug export)."""
+    _codes(Xq, packed_bytes8(M, K), "Xq"); _codes(Wq, packed_bytes8(N, K), "Wq")
     acc = torch.empty((M, N), dtype=torch.int32, device=Xq.device) if acc is None else acc
     _check(load().convrot_w8a8_gemm_i32(_ptr(Xq), _ptr(Wq), M, N, K, _ptr(acc), _stream(stream)),
            "convrot_w8a8_gemm_i32")
@@ -264,11 +269,10 @@ def convlinear8bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Ten
                            Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                            bias: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """X bf16 [M, K], prepared 8-bit weight -> Y bf16 [M, N]; `workspace`: uint8 tensor of workspace_bytes8(M, K)."""
-    _dev(X, torch.bfloat16, "X"); _dev(Wq, torch.int8, "Wq"); _dev(w_scale, torch.float32, "w_scale")
+    _dev(X, torch.bfloat16, "X"); _dev(w_scale, torch.float32, "w_scale")
     M, K = X.shape
-    N = Wq.shape[0]
-    if Wq.shape[1] != K:
-        raise ValueError("K mismatch")
+    N = w_scale.shape[0]
+    _codes(Wq, packed_bytes8(N, K), "Wq")
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if Y is None else Y
     if workspace is None:
         workspace = torch.empty((max(workspace_bytes8(M, K), 256),), dtype=torch.uint8, device=X.device)

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconvrot.so")
-SOURCES = ("convrot_api.hip", "rotquant.hip", "gemm_w4a4.hip", "gemm_w4a4_generic.hip", "gemm_w8a8.hip")
+SOURCES = ("convrot_api.hip", "rotquant.hip", "gemm_w4a4.hip", "gemm_w8a8.hip")
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

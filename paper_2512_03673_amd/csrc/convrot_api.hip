@@ -4,6 +4,7 @@
 
 #include "convrot.h"
 #include "convrot_internal.h"
+#include "panel_layout.h"
 
 namespace {
 
@@ -25,7 +26,7 @@ int check_rotquant(const void *in, int64_t rows, int64_t K, int group, const voi
     if (int rc = check_k(K)) return rc;
     if (K % group != 0) return CONVROT_ERR_SHAPE;
     if (missing(in, rows) || missing(out, rows) || missing(scale, rows)) return CONVROT_ERR_NULL;
-    if (!aligned(in, 16) || !aligned(out, 16) || !aligned(scale, 4)) return CONVROT_ERR_ALIGN;
+    if (!aligned(in, 16) || !aligned(out, 256) || !aligned(scale, 4)) return CONVROT_ERR_ALIGN;
     return CONVROT_OK;
 }
 
@@ -34,7 +35,7 @@ int check_gemm(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K, 
     if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
     if (int rc = check_k(K)) return rc;
     if (missing(Xq, M) || missing(Wq, N) || missing(out, M * N)) return CONVROT_ERR_NULL;
-    if (!aligned(Xq, 16) || !aligned(Wq, 16) || !aligned(out, out_align)) return CONVROT_ERR_ALIGN;
+    if (!aligned(Xq, 256) || !aligned(Wq, 256) || !aligned(out, out_align)) return CONVROT_ERR_ALIGN;
     return CONVROT_OK;
 }
 
@@ -49,7 +50,7 @@ const char *convrot_status_string(int status)
     switch (status) {
         case CONVROT_OK: return "ok";
         case CONVROT_ERR_NULL: return "null pointer";
-        case CONVROT_ERR_SHAPE: return "bad shape (need M,N >= 0, 0 < K <= 65536, K % 32 == 0 (8-bit: K % 64 == 0), K % group == 0)";
+        case CONVROT_ERR_SHAPE: return "bad shape (need M,N >= 0, 0 < K <= 65536, K % 32 == 0, K % group == 0)";
         case CONVROT_ERR_GROUP: return "bad group size (need 4, 16, 64, 256 or 1024)";
         case CONVROT_ERR_ALIGN: return "misaligned pointer";
         case CONVROT_ERR_WORKSPACE: return "workspace too small";
@@ -63,13 +64,19 @@ int convrot_version(void) { return CONVROT_VERSION; }
 size_t convrot_packed_bytes(int64_t rows, int64_t K)
 {
     if (rows < 0 || K <= 0 || (K & 1)) return 0;
-    return (size_t)rows * (size_t)(K / 2);
+    return (size_t)convrot::panel::matrix_bytes(rows, K / 2);
+}
+
+size_t convrot_packed_bytes8(int64_t rows, int64_t K)
+{
+    if (rows < 0 || K <= 0) return 0;
+    return (size_t)convrot::panel::matrix_bytes(rows, K);
 }
 
 size_t convrot_workspace_bytes(int64_t M, int64_t K)
 {
     if (M < 0 || K <= 0 || (K & 1)) return 0;
-    return round_up((size_t)M * (size_t)(K / 2), 256) + round_up((size_t)M * sizeof(float), 256);
+    return convrot_packed_bytes(M, K) + round_up((size_t)M * sizeof(float), 256);
 }
 
 int convrot_prepare_weight(const void *W_bf16, int64_t N, int64_t K, int group, void *Wq, float *w_scale,
@@ -114,13 +121,13 @@ int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
     if (missing(X_bf16, M) || missing(Wq, N) || missing(w_scale, N) || missing(Y_bf16, M * N) ||
         missing(workspace, M))
         return CONVROT_ERR_NULL;
-    if (!aligned(X_bf16, 16) || !aligned(Wq, 16) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
+    if (!aligned(X_bf16, 16) || !aligned(Wq, 256) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
         !aligned(bias_bf16, 2) || !aligned(workspace, 256))
         return CONVROT_ERR_ALIGN;
     if (workspace_bytes < convrot_workspace_bytes(M, K)) return CONVROT_ERR_WORKSPACE;
 
     uint8_t *xq = static_cast<uint8_t *>(workspace);
-    float *xs = reinterpret_cast<float *>(xq + round_up((size_t)M * (size_t)(K / 2), 256));
+    float *xs = reinterpret_cast<float *>(xq + convrot_packed_bytes(M, K));
     hipStream_t s = (hipStream_t)stream;
     if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, 4, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
     return from_hip(convrot::launch_gemm_w4a4(xq, xs, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr, s));
@@ -144,14 +151,13 @@ int convrot_rotated_absmax(const void *X_bf16, int64_t M, int64_t K, int group, 
 size_t convrot_workspace_bytes8(int64_t M, int64_t K)
 {
     if (M < 0 || K <= 0) return 0;
-    return round_up((size_t)M * (size_t)K, 256) + round_up((size_t)M * sizeof(float), 256);
+    return convrot_packed_bytes8(M, K) + round_up((size_t)M * sizeof(float), 256);
 }
 
 int convrot_prepare_weight8(const void *W_bf16, int64_t N, int64_t K, int group, void *Wq, float *w_scale,
                             void *stream)
 {
     if (int rc = check_rotquant(W_bf16, N, K, group, Wq, w_scale)) return rc;
-    if (K % 64 != 0) return CONVROT_ERR_SHAPE;
     return from_hip(convrot::launch_rotquant(W_bf16, N, K, group, 8, Wq, w_scale, (hipStream_t)stream));
 }
 
@@ -159,7 +165,6 @@ int convrot_rotquant_act8(const void *X_bf16, int64_t M, int64_t K, int group, v
                           void *stream)
 {
     if (int rc = check_rotquant(X_bf16, M, K, group, Xq, x_scale)) return rc;
-    if (K % 64 != 0) return CONVROT_ERR_SHAPE;
     return from_hip(convrot::launch_rotquant(X_bf16, M, K, group, 8, Xq, x_scale, (hipStream_t)stream));
 }
 
@@ -167,7 +172,6 @@ int convrot_w8a8_gemm_dequant(const void *Xq, const float *x_scale, const void *
                               const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16, void *stream)
 {
     if (int rc = check_gemm(Xq, Wq, M, N, K, Y_bf16, 16)) return rc;
-    if (K % 64 != 0) return CONVROT_ERR_SHAPE;
     if (missing(x_scale, M) || missing(w_scale, N)) return CONVROT_ERR_NULL;
     if (!aligned(x_scale, 4) || !aligned(w_scale, 4) || !aligned(bias_bf16, 2)) return CONVROT_ERR_ALIGN;
     return from_hip(convrot::launch_gemm_w8a8(Xq, x_scale, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr,
@@ -178,7 +182,6 @@ int convrot_w8a8_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, 
                           void *stream)
 {
     if (int rc = check_gemm(Xq, Wq, M, N, K, acc, 16)) return rc;
-    if (K % 64 != 0) return CONVROT_ERR_SHAPE;
     return from_hip(convrot::launch_gemm_w8a8(Xq, nullptr, Wq, nullptr, nullptr, M, N, K, nullptr, acc,
                                               (hipStream_t)stream));
 }
@@ -190,17 +193,17 @@ int convlinear8bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
     if (int rc = check_group(group)) return rc;
     if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
     if (int rc = check_k(K)) return rc;
-    if (K % group != 0 || K % 64 != 0) return CONVROT_ERR_SHAPE;
+    if (K % group != 0) return CONVROT_ERR_SHAPE;
     if (missing(X_bf16, M) || missing(Wq, N) || missing(w_scale, N) || missing(Y_bf16, M * N) ||
         missing(workspace, M))
         return CONVROT_ERR_NULL;
-    if (!aligned(X_bf16, 16) || !aligned(Wq, 16) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
+    if (!aligned(X_bf16, 16) || !aligned(Wq, 256) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
         !aligned(bias_bf16, 2) || !aligned(workspace, 256))
         return CONVROT_ERR_ALIGN;
     if (workspace_bytes < convrot_workspace_bytes8(M, K)) return CONVROT_ERR_WORKSPACE;
 
     uint8_t *xq = static_cast<uint8_t *>(workspace);
-    float *xs = reinterpret_cast<float *>(xq + round_up((size_t)M * (size_t)K, 256));
+    float *xs = reinterpret_cast<float *>(xq + convrot_packed_bytes8(M, K));
     hipStream_t s = (hipStream_t)stream;
     if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, 8, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
     return from_hip(convrot::launch_gemm_w8a8(xq, xs, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr, s));

@@ -7,7 +7,7 @@
 namespace convrot {
 
 // Rotate + quantise + pack `rows` rows of K bf16 values (group in {4,16,64,256,1024}; bits 4: two codes
-// per byte, bits 8: one int8 per code).
+// per byte, bits 8: one int8 per code).  Xq is written in the panel layout (panel_layout.h).
 hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, int bits, void *Xq, float *scale,
                            hipStream_t stream);
 
@@ -15,14 +15,14 @@ hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, in
 hipError_t launch_rotated_absmax(const void *X, int64_t rows, int64_t K, int group, int kind, float *out,
                                  hipStream_t stream);
 
-// W4A4 GEMM on packed codes.  Exactly one of Y_bf16 / acc_i32 is non-null:
+// W4A4 GEMM on packed codes in the panel layout.  Exactly one of Y_bf16 / acc_i32 is non-null:
 //   Y_bf16 : dequantised bf16 output (needs x_scale, w_scale; bias_bf16 [N] or null)
 //   acc_i32: raw int32 accumulators
 hipError_t launch_gemm_w4a4(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
                             const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16,
                             int32_t *acc_i32, hipStream_t stream);
 
-// W8A8 GEMM on int8 codes [rows, K]; same contract as launch_gemm_w4a4.  K % 64 == 0.
+// W8A8 GEMM on int8 codes in the panel layout; same contract as launch_gemm_w4a4.
 hipError_t launch_gemm_w8a8(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
                             const void *bias_bf16, int64_t M, int64_t N, int64_t K, void *Y_bf16,
                             int32_t *acc_i32, hipStream_t stream);

@@ -1,5 +1,5 @@
-// Shared pieces of the two W4A4 GEMM kernels of libconvrot (tile shape, LDS swizzle, LDS-direct
-// loads, tile order).  See gemm_w4a4.hip for the description of the method.
+// Shared pieces of the GEMM kernels of libconvrot, 4-bit and 8-bit (LDS swizzle, LDS-direct loads,
+// tile order).  See gemm_w4a4.hip for the description of the method.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -14,23 +14,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 256, BN = 256;        // block tile
-constexpr int kThreads = 256;            // 4 wavefronts, 2 x 2
-constexpr int WTM = 128, WTN = 128;      // wavefront tile
-constexpr int FM = WTM / 32, FN = WTN / 32;
-constexpr int kRowBytes = 64;                             // packed bytes of K per row per stage (64 B = 128 codes)
-constexpr int kStages = 4;
-constexpr int kPieces = kRowBytes / 16;                   // 16-byte pieces per LDS row
-constexpr int kSubSteps = kRowBytes / 32;                 // K64 steps (one ds_read_b128 per fragment) per stage
-constexpr int kStageBytes = (BM + BN) * kRowBytes;
-constexpr int kRingBytes = kStages * kStageBytes;         // 128 KB
-constexpr int kChunksPerWave = kStageBytes / 1024 / 4;    // 1 KB LDS-direct loads per wavefront per stage
-constexpr int kRowsPerChunk = 1024 / kRowBytes;
+constexpr int kRowBytes = 64;                 // bytes of K per row per stage: 128 4-bit codes or 64 8-bit codes
+constexpr int kSubSteps = kRowBytes / 32;     // MFMA K-steps of 32 bytes per row (one ds_read_b128 per fragment) per stage
 constexpr int kNumXcd = 8;
-
-static_assert(kChunksPerWave * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
-static_assert(kSubSteps % 2 == 0, "operand double-buffer parity must return to 0 every stage");
-static_assert(kChunksPerWave <= 24 && FM + FN == 8, "slot plan of a K64 step");
 
 __device__ __forceinline__ uint32_t nib_lo(uint32_t p) { return (p << 4) & 0xF0F0F0F0u; }
 __device__ __forceinline__ uint32_t nib_hi(uint32_t p) { return p & 0xF0F0F0F0u; }
@@ -53,18 +39,6 @@ __device__ __forceinline__ void lds_dma16(const uint8_t *base, uint32_t lane_off
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory");
 }
-__device__ __forceinline__ void lds_dma16_addr(const uint8_t *lane_ptr, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(lane_ptr), "s"(lds_addr) : "memory");
-}
-// global_load_lds_dword: lane l copies 4 bytes from its global address to LDS address M0 + 4 l.
-__device__ __forceinline__ void lds_dma4_addr(const void *lane_ptr, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-                 :: "v"(lane_ptr), "s"(lds_addr) : "memory");
-}
-
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
@@ -95,10 +69,5 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
 }
 
 }  // namespace gemm
-
-// One output tile per block, any K the library accepts (gemm_w4a4_generic.hip).
-hipError_t launch_gemm_w4a4_generic(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,
-                                    const void *bias_bf16, int M, int N, int K, void *Y_bf16, int32_t *acc_i32,
-                                    hipStream_t stream);
 
 }  // namespace convrot

@@ -19,7 +19,10 @@
 // blocks share a compute unit: while one runs its prologue or epilogue, or waits at a barrier,
 // the other keeps the MFMA pipe busy.  Packed codes travel HBM -> LDS with
 // global_load_lds_dwordx4 (no register staging) into a ring of 3 stages of 128 codes (64 bytes)
-// of K; the codes stay packed in LDS and are widened in registers after ds_read_b128, 3 VALU
+// of K.  The operands sit in HBM as 1 KB panels of 16 rows x 64 bytes (panel_layout.h), so that one such
+// instruction - 16 tile rows of one stage - reads one contiguous kilobyte: the same bytes fetched as
+// sixteen 64-byte row pieces move at under half the rate and held the whole loop back.
+// The codes stay packed in LDS and are widened in registers after ds_read_b128, 3 VALU
 // operations per packed dword.  LDS rows are 64 bytes; the four 16-byte pieces of a row are
 // XOR-swizzled by row so that the fragment reads (32 consecutive rows, one piece) touch every
 // bank once.  The swizzle is applied on the global side: an LDS-direct load writes lane l at
@@ -29,11 +32,11 @@
 // with four consecutive n for one m; the epilogue scales, rounds to bf16, transposes through LDS
 // and writes 16 bytes per lane, 128 contiguous bytes per output row.
 //
-// This kernel takes K % 128 == 0 (every stage of the ring whole); other K go to the kernel in
-// gemm_w4a4_generic.hip.
-#include "gemm_w4a4_common.h"
+// Any K the library accepts: the panel layout pads the last stage of a row with zero codes.
+#include "gemm_common.h"
 
 #include "convrot_internal.h"
+#include "panel_layout.h"
 
 namespace convrot {
 
@@ -85,9 +88,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     const int m0 = tm * TM, n0 = tn * TN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
-    const int Kb = K >> 1;              // packed bytes per row
-    const int KT = Kb / kRowBytes;      // stages, all whole (host-checked)
-
+    const int KT = (int)panel::k_panels(K >> 1);   // stages = K-panels per row; the last one is zero-padded
     // ---- dequantisation scales of the tile's rows and columns: thread t fetches x_scale[m0 + t] and
     // w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
     // the ring) once the loop is over.
@@ -101,16 +102,17 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     }
 
     // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
-    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..383 are W); lane l fills slot l & 3 of row l >> 2.
-    const uint8_t *xtile = Xq + (int64_t)m0 * Kb;
-    const uint8_t *wtile = Wq + (int64_t)n0 * Kb;
-    uint32_t goff[kChunks];   // byte offset of this lane's piece inside the operand tile, stage 0
+    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..383 are W), which is one 1 KB panel of the operand
+    // (panel_layout.h), K-panels of the same rows 1 KB apart; lane l fills slot l & 3 of row l >> 2.
+    const uint8_t *xtile = Xq + (int64_t)(m0 / panel::kRows) * KT * panel::kBytes;
+    const uint8_t *wtile = Wq + (int64_t)(n0 / panel::kRows) * KT * panel::kBytes;
+    uint32_t goff[kChunks];   // byte offset of this lane's piece inside the operand's tile rows, stage 0
 #pragma unroll
     for (int i = 0; i < kChunks; ++i) {
         const int row_t = 16 * (wave + 4 * i) + lane / 4;
         const int piece = (lane % 4) ^ swz(row_t);
         const int r = i < kXChunks ? min(row_t, M - 1 - m0) : min(row_t - TM, N - 1 - n0);   // edge rows re-read the last valid row
-        goff[i] = (uint32_t)r * (uint32_t)Kb + piece * 16;
+        goff[i] = (uint32_t)(r / panel::kRows) * (uint32_t)KT * panel::kBytes + (r % panel::kRows) * kRowBytes + piece * 16;
     }
     // LDS-direct loads are issued from inline assembly so that the compiler does not serialise every
     // later LDS read behind them; completion is tracked by hand with vmcnt.
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     // chunk i of this wavefront's share of stage kt; chunk wave + 4 i sits 4096 i further on
     auto load_chunk = [&](int kt, int i) {
         const uint32_t sl = wave_lds + ((unsigned)kt % kStages) * kStageBytes;
-        lds_dma16((i < kXChunks ? xtile : wtile) + (uint32_t)kt * kRowBytes, goff[i], sl + i * 4096);
+        lds_dma16((i < kXChunks ? xtile : wtile) + (uint32_t)kt * panel::kBytes, goff[i], sl + i * 4096);
     };
 
     // ---- LDS -> registers: fragment of 32 rows x 32 packed codes per lane-half
@@ -368,9 +370,6 @@ hipError_t launch_gemm_w4a4(const void *Xq, const float *x_scale, const void *Wq
                             int32_t *acc_i32, hipStream_t stream)
 {
     if (M == 0 || N == 0) return hipSuccess;
-    if (K % (2 * kRowBytes) != 0)   // a ragged last stage: the general kernel zero-fills it
-        return launch_gemm_w4a4_generic(Xq, x_scale, Wq, w_scale, bias_bf16, (int)M, (int)N, (int)K, Y_bf16, acc_i32,
-                                        stream);
     if (acc_i32)
         return launch_one<true>(Xq, x_scale, Wq, w_scale, nullptr, (int)M, (int)N, (int)K, nullptr, acc_i32, stream);
     return launch_one<false>(Xq, x_scale, Wq, w_scale, bias_bf16, (int)M, (int)N, (int)K, Y_bf16, nullptr, stream);

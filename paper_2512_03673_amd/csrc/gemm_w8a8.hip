@@ -8,10 +8,12 @@
 // LDS-direct loads into a swizzled ring of 3 stages, one memory instruction per MFMA slot, scales and
 // bias parked in LDS, LDS-transposed bf16 epilogue) minus the widening: a 16-byte fragment read from
 // LDS is an operand of v_mfma_i32_32x32x32_i8 as it stands.  A stage is 64 bytes = 64 codes of K per
-// row, i.e. two MFMAs per accumulator tile; K % 64 == 0.  |acc| <= 127^2 K < 2^31 for K <= 65536.
-#include "gemm_w4a4_common.h"
+// row, i.e. two MFMAs per accumulator tile; the panel layout of the operands (panel_layout.h) pads the
+// last stage with zero codes.  |acc| <= 127^2 K < 2^31 for K <= 65536.
+#include "gemm_common.h"
 
 #include "convrot_internal.h"
+#include "panel_layout.h"
 
 namespace convrot {
 
@@ -61,8 +63,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     const int m0 = tm * TM, n0 = tn * TN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
-    const int Kb = K;                   // bytes per row
-    const int KT = Kb / kRowBytes;      // stages, all whole (host-checked)
+    const int KT = (int)panel::k_panels(K);   // stages = K-panels per row; the last one is zero-padded
 
     // ---- dequantisation scales of the tile's rows and columns: thread t fetches x_scale[m0 + t] and
     // w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
@@ -77,16 +78,17 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     }
 
     // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
-    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..383 are W); lane l fills slot l & 3 of row l >> 2.
-    const uint8_t *xtile = Xq + (int64_t)m0 * Kb;
-    const uint8_t *wtile = Wq + (int64_t)n0 * Kb;
-    uint32_t goff[kChunks];   // byte offset of this lane's piece inside the operand tile, stage 0
+    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..383 are W), which is one 1 KB panel of the operand
+    // (panel_layout.h), K-panels of the same rows 1 KB apart; lane l fills slot l & 3 of row l >> 2.
+    const uint8_t *xtile = Xq + (int64_t)(m0 / panel::kRows) * KT * panel::kBytes;
+    const uint8_t *wtile = Wq + (int64_t)(n0 / panel::kRows) * KT * panel::kBytes;
+    uint32_t goff[kChunks];   // byte offset of this lane's piece inside the operand's tile rows, stage 0
 #pragma unroll
     for (int i = 0; i < kChunks; ++i) {
         const int row_t = 16 * (wave + 4 * i) + lane / 4;
         const int piece = (lane % 4) ^ swz(row_t);
         const int r = i < kXChunks ? min(row_t, M - 1 - m0) : min(row_t - TM, N - 1 - n0);   // edge rows re-read the last valid row
-        goff[i] = (uint32_t)r * (uint32_t)Kb + piece * 16;
+        goff[i] = (uint32_t)(r / panel::kRows) * (uint32_t)KT * panel::kBytes + (r % panel::kRows) * kRowBytes + piece * 16;
     }
     // LDS-direct loads are issued from inline assembly so that the compiler does not serialise every
     // later LDS read behind them; completion is tracked by hand with vmcnt.
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     // chunk i of this wavefront's share of stage kt; chunk wave + 4 i sits 4096 i further on
     auto load_chunk = [&](int kt, int i) {
         const uint32_t sl = wave_lds + ((unsigned)kt % kStages) * kStageBytes;
-        lds_dma16((i < kXChunks ? xtile : wtile) + (uint32_t)kt * kRowBytes, goff[i], sl + i * 4096);
+        lds_dma16((i < kXChunks ? xtile : wtile) + (uint32_t)kt * panel::kBytes, goff[i], sl + i * 4096);
     };
 
     // ---- LDS -> registers: fragment of 32 rows x 32 packed codes per lane-half
@@ -311,7 +313,6 @@ hipError_t launch_gemm_w8a8(const void *Xq, const float *x_scale, const void *Wq
                             int32_t *acc_i32, hipStream_t stream)
 {
     if (M == 0 || N == 0) return hipSuccess;
-    if (K % kRowBytes != 0) return hipErrorInvalidValue;   // host-checked by the caller
     if (acc_i32)
         return launch_one<true>(Xq, x_scale, Wq, w_scale, nullptr, (int)M, (int)N, (int)K, nullptr, acc_i32, stream);
     return launch_one<false>(Xq, x_scale, Wq, w_scale, bias_bf16, (int)M, (int)N, (int)K, Y_bf16, nullptr, stream);

@@ -21,10 +21,14 @@
 // q = rne(z / (2^k s)) decided exactly from two bracketing multiply-adds, with an exact-residual
 // fallback for the few wavefronts that hold a (near-)tie (see the comment at the code).
 // |z| / (2^k s) <= 7 (1 + 2^-22), so no clamp is needed.
+//
+// Output.  The codes leave in the panel layout the GEMM loads from (panel_layout.h): a lane's unit is
+// 8 (or 16) bytes of a 64-byte panel row, so 8 (or 4) neighbouring lanes fill one panel row.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "convrot_internal.h"
+#include "panel_layout.h"
 
 namespace convrot {
 
@@ -99,7 +103,7 @@ constexpr float group_norm() { return G == 4 ? 0.5f : G == 16 ? 0.25f : G == 64 
 
 }  // namespace
 
-// grid.x = ceil(rows / rows_per_block); block = rows_per_block * T threads, T = 64 * waves_per_row.
+// grid.x = 8 * ceil(rows / 128) * 16 / rows_per_block; block = rows_per_block * T threads, T = 64 * waves_per_row.
 // BITS = 4: two codes per byte, [-7, 7]; BITS = 8 (the W8A8 variant of the layer): one int8 per code, [-127, 127].
 template <int G, int U, int BLOCK, int BITS>
 __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
@@ -112,7 +116,12 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
     const int rib = tid / T;               // row inside the block
     const int t = tid - rib * T;           // lane index inside the row
     const int rows_per_block = BLOCK / T;
-    const int64_t row = (int64_t)blockIdx.x * rows_per_block + rib;
+    // Blocks are dealt round-robin to the 8 XCDs, each with an L2 of its own.  The 16 rows of an output
+    // panel go to consecutive blocks of one XCD, so that the 64-byte row pieces of a panel meet in one
+    // L2 and leave it as whole lines.
+    const int bpp = panel::kRows / rows_per_block;            // blocks per row panel
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int64_t row = ((int64_t)(idx / bpp) * 8 + xcd) * panel::kRows + (idx % bpp) * rows_per_block + rib;
     const bool row_ok = row < rows;
     const int units = K / kUnit;
 
@@ -230,14 +239,24 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
                 code[w] = d;
             }
         }
+        // Panel layout: 1 KB panels of 16 rows x 64 bytes.  A unit is 8 bytes (4-bit) or 16 bytes (8-bit)
+        // of its row; units past the row's end inside its last K-panel are stored as zero codes.
         const int unit = i * T + tf;
-        if (row_ok && unit < units) {
+        constexpr int kUnitBytes = kUnit * BITS / 8;
+        constexpr int kUnitsPerPanelRow = panel::kRowBytes / kUnitBytes;
+        const int padded_units = (units + kUnitsPerPanelRow - 1) / kUnitsPerPanelRow * kUnitsPerPanelRow;
+        if (row_ok && unit < padded_units) {
+            if (unit >= units) {
+#pragma unroll
+                for (int w = 0; w < kDwords; ++w) code[w] = 0;
+            }
+            uint8_t *o = Xq + ((row >> 4) * (int64_t)(padded_units / kUnitsPerPanelRow) + unit / kUnitsPerPanelRow) * panel::kBytes +
+                         (int)(row & 15) * panel::kRowBytes + (unit % kUnitsPerPanelRow) * kUnitBytes;
+            // plain (cacheable) stores: the pieces of a line are merged in L2
             if constexpr (BITS == 4) {
-                u32x2 *o = reinterpret_cast<u32x2 *>(Xq + row * (int64_t)(K / 2) + (int64_t)unit * (kUnit / 2));
-                __builtin_nontemporal_store(u32x2{code[0], code[1]}, o);
+                *reinterpret_cast<u32x2 *>(o) = u32x2{code[0], code[1]};
             } else {
-                u32x4 *o = reinterpret_cast<u32x4 *>(Xq + row * (int64_t)K + (int64_t)unit * kUnit);
-                __builtin_nontemporal_store(u32x4{code[0], code[1], code[2], code[3]}, o);
+                *reinterpret_cast<u32x4 *>(o) = u32x4{code[0], code[1], code[2], code[3]};
             }
         }
     }
@@ -318,16 +337,17 @@ hipError_t launch_gu(const void *X, int64_t rows, int K, int waves_per_row, void
                      hipStream_t stream)
 {
     const int T = 64 * waves_per_row;
+    // grid: 8 XCDs x whole row panels per XCD x blocks per panel (see the row mapping in the kernel)
+    auto grid_for = [&](int rpb) { return (unsigned)(((rows + 127) / 128) * 8 * (panel::kRows / rpb)); };
     if (T <= 256) {
         const int rpb = 256 / T;
-        const unsigned grid = (unsigned)((rows + rpb - 1) / rpb);
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 256, BITS>), dim3(grid), dim3(256), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 256, BITS>), dim3(grid_for(rpb)), dim3(256), 0, stream,
                            (const uint16_t *)X, rows, K, T, (uint8_t *)Xq, scale);
     } else if (T <= 512) {
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 512, BITS>), dim3((unsigned)rows), dim3(512), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 512, BITS>), dim3(grid_for(1)), dim3(512), 0, stream,
                            (const uint16_t *)X, rows, K, 512, (uint8_t *)Xq, scale);
     } else {
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 1024, BITS>), dim3((unsigned)rows), dim3(1024), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 1024, BITS>), dim3(grid_for(1)), dim3(1024), 0, stream,
                            (const uint16_t *)X, rows, K, 1024, (uint8_t *)Xq, scale);
     }
     return hipGetLastError();

@@ -16,8 +16,31 @@ def bits_to_f64(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
-def unpack_host(packed: np.ndarray) -> np.ndarray:
-    """Canonical packed layout -> int8 codes (numpy, test side)."""
+def from_panels(buf: np.ndarray, rows: int, row_bytes: int) -> np.ndarray:
+    """The library's code-matrix layout (1 KB panels of 16 rows x 64 bytes, K-panels of the same rows
+    adjacent) -> row-major uint8 [rows, row_bytes].  Checks that the K padding holds zero codes."""
+    rp, kp = -(-rows // 16), -(-row_bytes // 64)
+    buf = np.ascontiguousarray(buf).view(np.uint8).ravel()
+    assert buf.size >= rp * kp * 1024, "code matrix shorter than its panel layout"
+    a = buf[:rp * kp * 1024].reshape(rp, kp, 16, 64).transpose(0, 2, 1, 3).reshape(rp * 16, kp * 64)
+    assert not a[:rows, row_bytes:].any(), "K padding of a code matrix must be zero codes"
+    return np.ascontiguousarray(a[:rows, :row_bytes])
+
+
+def to_panels(mat: np.ndarray, junk: int = 0x5A) -> np.ndarray:
+    """Row-major byte matrix -> panel layout.  The K padding is zero, as the library requires; the padding
+    rows of the last row panel are filled with `junk`, which the library must never look at."""
+    mat = np.ascontiguousarray(mat).view(np.uint8)
+    rows, row_bytes = mat.shape
+    rp, kp = -(-rows // 16), -(-row_bytes // 64)
+    a = np.full((rp * 16, kp * 64), junk, dtype=np.uint8)
+    a[:rows] = 0
+    a[:rows, :row_bytes] = mat
+    return np.ascontiguousarray(a.reshape(rp, 16, kp, 64).transpose(0, 2, 1, 3)).ravel()
+
+
+def unpack_nibbles(packed: np.ndarray) -> np.ndarray:
+    """Row-major packed 4-bit codes [rows, K/2] -> int8 codes [rows, K] (numpy, test side)."""
     lo = (packed & 0xF).astype(np.int8)
     hi = (packed >> 4).astype(np.int8)
     lo = np.where(lo >= 8, lo - 16, lo).astype(np.int8)
@@ -26,6 +49,32 @@ def unpack_host(packed: np.ndarray) -> np.ndarray:
     out[:, 0::2] = lo
     out[:, 1::2] = hi
     return out
+
+
+def unpack_host(buf, rows: int, K: int) -> np.ndarray:
+    """4-bit code matrix as the library stores it (tensor or array) -> int8 codes [rows, K]."""
+    if isinstance(buf, torch.Tensor):
+        buf = buf.cpu().numpy()
+    return unpack_nibbles(from_panels(buf, rows, K // 2))
+
+
+def unpack_host8(buf, rows: int, K: int) -> np.ndarray:
+    """8-bit code matrix as the library stores it -> int8 codes [rows, K]."""
+    if isinstance(buf, torch.Tensor):
+        buf = buf.cpu().numpy()
+    return from_panels(buf, rows, K).view(np.int8)
+
+
+def codes4_to_dev(codes: np.ndarray) -> torch.Tensor:
+    """int8 codes [rows, K] in [-7, 7] -> 4-bit code matrix on the GPU, in the library's layout."""
+    c = codes.astype(np.uint8) & 0xF
+    packed = (c[:, 0::2] | (c[:, 1::2] << 4)).astype(np.uint8)
+    return torch.from_numpy(to_panels(packed)).cuda()
+
+
+def codes8_to_dev(codes: np.ndarray) -> torch.Tensor:
+    """int8 codes [rows, K] -> 8-bit code matrix on the GPU, in the library's layout."""
+    return torch.from_numpy(to_panels(codes.astype(np.int8).view(np.uint8))).cuda()
 
 
 def ulp_diff_f32(a: np.ndarray, b: np.ndarray) -> np.ndarray:

@@ -28,7 +28,7 @@ def declared_symbols():
 def test_header_symbols_are_exported(lib):
     from paper_2512_03673_amd import binding
     names = declared_symbols()
-    assert len(names) == 16
+    assert len(names) == 17
     assert sorted(binding.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -36,14 +36,20 @@ def test_header_symbols_are_exported(lib):
 
 def test_size_queries_and_strings(lib):
     from paper_2512_03673_amd import binding as b
-    assert b.version() == 200
+    assert b.version() == 300
+    # code matrices: 1 KB panels of 16 rows x 64 bytes, rows and K padded up to whole panels
     assert b.packed_bytes(4608, 3072) == 4608 * 1536
+    assert b.packed_bytes(37, 96) == 3 * 1 * 1024 and b.packed_bytes(3, 32) == 1024
+    assert b.packed_bytes(16, 128) == 1024 and b.packed_bytes(17, 160) == 2 * 2 * 1024
+    assert b.packed_bytes(0, 32) == 0
     assert b.packed_bytes(-1, 32) == 0 and b.packed_bytes(4, 33) == 0
-    # codes rounded up to 256 B + scales rounded up to 256 B
+    assert b.packed_bytes8(37, 96) == 3 * 2 * 1024 and b.packed_bytes8(4608, 3072) == 4608 * 3072
+    # code matrix + scales rounded up to 256 B
     assert b.workspace_bytes(4608, 3072) == 4608 * 1536 + 4608 * 4
-    assert b.workspace_bytes(3, 32) == 256 + 256
+    assert b.workspace_bytes(3, 32) == 1024 + 256
     assert b.workspace_bytes(0, 32) == 0
     assert b.workspace_bytes8(4608, 3072) == 4608 * 3072 + 4608 * 4
+    assert b.workspace_bytes8(3, 32) == 1024 + 256
     assert b.status_string(0) == "ok"
     assert "group" in b.status_string(-3)
     assert b.status_string(-99) == "unknown status"
@@ -84,16 +90,16 @@ def test_argument_validation_without_a_device(lib):
     assert fw(A, A, A, A, 4, 4, 1024, 16, A, A + 16, 1 << 20, None) == -4
     assert fw(A, A, A, A + 1, 4, 4, 1024, 16, A, A, 1 << 20, None) == -4
     assert fw(A, A, A, None, 4, 4, 1024, 16, A, A, 100, None) == -5
-    # W8A8 variant: same validation, K % 64 == 0 in addition
+    # W8A8 variant: same validation
     f8, g8, fw8 = lib.convrot_rotquant_act8, lib.convrot_w8a8_gemm_dequant, lib.convlinear8bit_forward
-    assert f8(A, 4, 96, 16, A, A, None) == -2            # K % 64 != 0
+    assert f8(A, 4, 48, 16, A, A, None) == -2            # K % 32 != 0
     assert f8(None, 4, 1024, 16, A, A, None) == -1
     assert lib.convrot_prepare_weight8(A, 4, 1024, 5, A, A, None) == -3
-    assert g8(A, A, A, A, None, 4, 4, 96, A, None) == -2
+    assert g8(A, A, A, A, None, 4, 4, 48, A, None) == -2
     assert g8(A, None, A, A, None, 4, 4, 1024, A, None) == -1
     assert lib.convrot_w8a8_gemm_i32(A, A, 4, 4, 1024, None, None) == -1
     assert fw8(A, A, A, None, 4, 4, 1024, 16, A, A, 100, None) == -5
-    assert fw8(A, A, A, None, 4, 4, 1056, 16, A, A, 1 << 20, None) == -2
+    assert fw8(A, A, A, None, 4, 4, 1040, 16, A, A, 1 << 20, None) == -2
     assert g8(A, A, A, A, None, 0, 4, 1024, A, None) == 0
     d = lib.convrot_rotated_absmax
     assert d(A, 4, 1024, 16, 3, A, None) == -3 and d(A, 4, 1024, 8, 1, A, None) == -3

@@ -13,7 +13,8 @@ import pytest
 import torch
 
 import oracle
-from gpu_util import bf16_to_host_bits, bf16_ulp_diff, check_codes, check_output, to_dev_bf16, unpack_host
+from gpu_util import (bf16_to_host_bits, bf16_ulp_diff, check_codes, check_output, codes4_to_dev, to_dev_bf16,
+                      unpack_host)
 from paper_2512_03673_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -55,16 +56,16 @@ def test_full_size_layer(cr, spec):
     xq, xs = cr.convrot_rotquant_act(xd, g)
     torch.cuda.synchronize()
     # the fused call leaves the activation codes and scales in its workspace: same bytes as the stand-alone call
-    nb = spec.M * spec.K // 2
-    assert torch.equal(ws_buf[:nb].view(spec.M, spec.K // 2), xq)
-    off = (nb + 255) // 256 * 256
-    assert torch.equal(ws_buf[off:off + 4 * spec.M].view(torch.float32), xs)
+    nb = cr.packed_bytes(spec.M, spec.K)
+    assert xq.numel() == nb and torch.equal(ws_buf[:nb], xq)
+    assert torch.equal(ws_buf[nb:nb + 4 * spec.M].view(torch.float32), xs)
 
     # ---- kernel A in full: weights and activations
     qwo, swo = oracle.rotquant(w, g)
-    fw, _ = check_codes(unpack_host(wq.cpu().numpy()), ws.cpu().numpy(), qwo, swo, f"{spec.name} W")
+    qwg = unpack_host(wq, spec.N, spec.K)
+    fw, _ = check_codes(qwg, ws.cpu().numpy(), qwo, swo, f"{spec.name} W")
     qxo, sxo = oracle.rotquant(x, g)
-    qxg = unpack_host(xq.cpu().numpy())
+    qxg = unpack_host(xq, spec.M, spec.K)
     fx, _ = check_codes(qxg, xs.cpu().numpy(), qxo, sxo, f"{spec.name} X")
     nz = np.abs(bf16_bits := wl.bf16_bits_to_f32(x)).max(axis=1) > 0
     assert (np.abs(qxg).max(axis=1)[nz] == 7).all()
@@ -75,9 +76,8 @@ def test_full_size_layer(cr, spec):
     # bf16 output against the oracle's end-to-end value
     rows = sample_rows(spec.M, seed=spec.K + spec.N)
     rt = torch.from_numpy(rows).cuda()
-    qwg = unpack_host(wq.cpu().numpy())
     acc_o = oracle.int_gemm(qxg[rows], qwg)
-    acc_g = cr.convrot_w4a4_gemm_i32(xq[rt].contiguous(), wq)
+    acc_g = cr.convrot_w4a4_gemm_i32(codes4_to_dev(qxg[rows]), wq, len(rows), spec.N, spec.K)
     torch.cuda.synchronize()
     assert np.array_equal(acc_g.cpu().numpy(), acc_o), f"{spec.name}: int32 GEMM differs"
 

@@ -9,8 +9,8 @@ import pytest
 import torch
 
 import oracle
-from gpu_util import (bf16_to_host_bits, bf16_ulp_diff, bits_to_f64, check_codes, check_output, to_dev_bf16,
-                      unpack_host)
+from gpu_util import (bf16_to_host_bits, bf16_ulp_diff, bits_to_f64, check_codes, check_output, codes4_to_dev,
+                      to_dev_bf16, unpack_host)
 from paper_2512_03673_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -30,7 +30,8 @@ def gpu_rotquant(cr, bits, g, weight=False):
     fn = cr.convrot_prepare_weight if weight else cr.convrot_rotquant_act
     q, s = fn(x, g)
     torch.cuda.synchronize()
-    return q.cpu().numpy(), s.cpu().numpy()
+    assert q.numel() == cr.packed_bytes(*bits.shape)
+    return unpack_host(q, *bits.shape), s.cpu().numpy()
 
 
 # ------------------------------------------------------------------ kernel A: rotate + quantise + pack
@@ -44,7 +45,7 @@ def test_rotquant_matches_oracle(cr, g, M, K):
     x = wl.make_activation(spec)
     q, s = gpu_rotquant(cr, x, g)
     qo, so = oracle.rotquant(x, g)
-    check_codes(unpack_host(q), s, qo, so, f"g={g} M={M} K={K}")
+    check_codes(q, s, qo, so, f"g={g} M={M} K={K}")
 
 
 @pytest.mark.parametrize("g", (4, 16, 64, 256))
@@ -56,7 +57,7 @@ def test_rotquant_small_k_multiples_of_32(cr, g):
         x = wl.f32_to_bf16_bits(rng.standard_normal((19, K)).astype(np.float32))
         q, s = gpu_rotquant(cr, x, g)
         qo, so = oracle.rotquant(x, g)
-        check_codes(unpack_host(q), s, qo, so, f"g={g} K={K}")
+        check_codes(q, s, qo, so, f"g={g} K={K}")
 
 
 @pytest.mark.parametrize("g", GROUPS)
@@ -70,9 +71,24 @@ def test_rotquant_closed_forms_on_gpu(cr, g):
     bits = wl.f32_to_bf16_bits(x)
     q, s = gpu_rotquant(cr, bits, g)
     qo, so = oracle.rotquant(bits, g)
-    assert np.array_equal(unpack_host(q), qo)
+    assert np.array_equal(q, qo)
     assert np.array_equal(s, so)
     assert s[2] == np.float32(1.0) and not q[2].any()
+
+
+def test_rotquant_leaves_padding_rows_alone_and_zeroes_k_padding(cr):
+    # 37 rows of K = 96: 3 row panels (the last with 5 valid rows), one K-panel of 48 code bytes + 16 of padding
+    M, K, g = 37, 96, 16
+    rng = np.random.default_rng(5)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    q = torch.full((cr.packed_bytes(M, K),), 0xAB, dtype=torch.uint8, device="cuda")
+    assert q.numel() == 3 * 1024
+    cr.convrot_rotquant_act(to_dev_bf16(x), g, q)
+    torch.cuda.synchronize()
+    raw = q.cpu().numpy().reshape(3, 16, 64)
+    assert (raw[2, 5:] == 0xAB).all(), "rows past M were written"
+    assert not raw.reshape(48, 64)[:M, 48:].any(), "K padding is not zero"
+    assert np.array_equal(unpack_host(q, M, K), oracle.rotquant(x, g)[0])
 
 
 def test_prepare_weight_is_the_same_operation(cr):
@@ -80,7 +96,7 @@ def test_prepare_weight_is_the_same_operation(cr):
     w = wl.make_weight(spec)
     q, s = gpu_rotquant(cr, w, 16, weight=True)
     qo, so = oracle.rotquant(w, 16)
-    check_codes(unpack_host(q), s, qo, so, "prepare_weight")
+    check_codes(q, s, qo, so, "prepare_weight")
 
 
 # ------------------------------------------------------------------ kernel B: integer GEMM
@@ -93,7 +109,7 @@ def test_gemm_i32_bit_exact(cr, M, N, K):
     # extreme rows: every product +-49, reaches the accumulator bound
     qx[0, :] = 7
     qw[0, :] = -7
-    acc = cr.convrot_w4a4_gemm_i32(torch.from_numpy(oracle.pack4(qx)).cuda(), torch.from_numpy(oracle.pack4(qw)).cuda())
+    acc = cr.convrot_w4a4_gemm_i32(codes4_to_dev(qx), codes4_to_dev(qw), M, N, K)
     torch.cuda.synchronize()
     assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
 
@@ -105,8 +121,8 @@ def test_gemm_dequant_on_identical_codes(cr, M, N, K):
     qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
     sx = np.exp(rng.uniform(-6, 2, M)).astype(np.float32)
     sw = np.exp(rng.uniform(-9, -4, N)).astype(np.float32)
-    y = cr.convrot_w4a4_gemm_dequant(torch.from_numpy(oracle.pack4(qx)).cuda(), torch.from_numpy(sx).cuda(),
-                                     torch.from_numpy(oracle.pack4(qw)).cuda(), torch.from_numpy(sw).cuda())
+    y = cr.convrot_w4a4_gemm_dequant(codes4_to_dev(qx), torch.from_numpy(sx).cuda(),
+                                     codes4_to_dev(qw), torch.from_numpy(sw).cuda(), K)
     torch.cuda.synchronize()
     yb = bf16_to_host_bits(y)
     yo = oracle.dequant(oracle.int_gemm(qx, qw), sx, sw)
@@ -125,9 +141,8 @@ def test_gemm_dequant_with_bias(cr, M, N, K):
     sx = np.exp(rng.uniform(-6, 2, M)).astype(np.float32)
     sw = np.exp(rng.uniform(-9, -4, N)).astype(np.float32)
     bias = wl.f32_to_bf16_bits((rng.standard_normal(N) * 0.5).astype(np.float32))
-    y = cr.convrot_w4a4_gemm_dequant(torch.from_numpy(oracle.pack4(qx)).cuda(), torch.from_numpy(sx).cuda(),
-                                     torch.from_numpy(oracle.pack4(qw)).cuda(), torch.from_numpy(sw).cuda(),
-                                     bias=to_dev_bf16(bias))
+    y = cr.convrot_w4a4_gemm_dequant(codes4_to_dev(qx), torch.from_numpy(sx).cuda(),
+                                     codes4_to_dev(qw), torch.from_numpy(sw).cuda(), K, bias=to_dev_bf16(bias))
     torch.cuda.synchronize()
     yb = bf16_to_host_bits(y)
     yo = oracle.dequant(oracle.int_gemm(qx, qw), sx, sw, bias)
@@ -171,7 +186,7 @@ def test_forward_equals_two_stage_calls(cr):
     wq, ws = cr.convrot_prepare_weight(to_dev_bf16(w), 16)
     y1 = cr.convlinear4bit_forward(xd, wq, ws, 16)
     xq, xs = cr.convrot_rotquant_act(xd, 16)
-    y2 = cr.convrot_w4a4_gemm_dequant(xq, xs, wq, ws)
+    y2 = cr.convrot_w4a4_gemm_dequant(xq, xs, wq, ws, 1024)
     torch.cuda.synchronize()
     assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
     check_output(bf16_to_host_bits(y1), oracle.convlinear4bit(x, w, 16), "forward ragged")
@@ -194,10 +209,10 @@ def test_forward_exact_on_representable_inputs(cr):
 def test_empty_inputs_are_noops(cr):
     dev = torch.device("cuda")
     xq, xs = cr.convrot_rotquant_act(torch.empty((0, 1024), dtype=torch.bfloat16, device=dev), 16)
-    assert xq.shape == (0, 512) and xs.shape == (0,)
-    wq = torch.zeros((8, 512), dtype=torch.uint8, device=dev)
+    assert xq.numel() == 0 and xs.shape == (0,)
+    wq = torch.zeros((cr.packed_bytes(8, 1024),), dtype=torch.uint8, device=dev)
     ws = torch.ones((8,), dtype=torch.float32, device=dev)
-    y = cr.convrot_w4a4_gemm_dequant(xq, xs, wq, ws)
+    y = cr.convrot_w4a4_gemm_dequant(xq, xs, wq, ws, 1024)
     assert y.shape == (0, 8)
     y = cr.convlinear4bit_forward(torch.empty((0, 1024), dtype=torch.bfloat16, device=dev), wq, ws, 16)
     assert y.shape == (0, 8)
@@ -207,7 +222,7 @@ def test_empty_inputs_are_noops(cr):
 def test_error_statuses_write_nothing(cr):
     dev = torch.device("cuda")
     x = torch.zeros((4, 1024), dtype=torch.bfloat16, device=dev)
-    q = torch.full((4, 512), 0xAB, dtype=torch.uint8, device=dev)
+    q = torch.full((cr.packed_bytes(4, 1024),), 0xAB, dtype=torch.uint8, device=dev)
     s = torch.full((4,), 5.0, dtype=torch.float32, device=dev)
     for g, want in ((8, -3), (0, -3), (2048, -3)):
         with pytest.raises(cr.ConvRotError) as e:
@@ -226,7 +241,7 @@ def test_error_statuses_write_nothing(cr):
     assert lib.convrot_rotquant_act(x.data_ptr() + 2, 4, 1024, 16, q.data_ptr(), s.data_ptr(), None) == -4
     ws = torch.empty((256,), dtype=torch.uint8, device=dev)
     y = torch.empty((4, 8), dtype=torch.bfloat16, device=dev)
-    wq = torch.zeros((8, 512), dtype=torch.uint8, device=dev)
+    wq = torch.zeros((cr.packed_bytes(8, 1024),), dtype=torch.uint8, device=dev)
     wsc = torch.ones((8,), dtype=torch.float32, device=dev)
     assert lib.convlinear4bit_forward(x.data_ptr(), wq.data_ptr(), wsc.data_ptr(), None, 4, 8, 1024, 16, y.data_ptr(),
                                       ws.data_ptr(), 256, None) == -5

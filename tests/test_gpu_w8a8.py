@@ -8,7 +8,8 @@ import pytest
 import torch
 
 import oracle
-from gpu_util import bf16_to_host_bits, bf16_ulp_diff, bits_to_f64, check_output, to_dev_bf16, ulp_diff_f32
+from gpu_util import (bf16_to_host_bits, bf16_ulp_diff, bits_to_f64, check_output, codes8_to_dev, to_dev_bf16,
+                      ulp_diff_f32, unpack_host8)
 from paper_2512_03673_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -41,7 +42,8 @@ def test_rotquant8_matches_oracle(cr, g, M, K):
     q, s = cr.convrot_rotquant_act8(to_dev_bf16(x), g)
     torch.cuda.synchronize()
     qo, so = oracle.rotquant(x, g, qmax=127)
-    frac = check_codes8(q.cpu().numpy(), s.cpu().numpy(), qo, so, f"g={g} M={M} K={K}")
+    assert q.numel() == cr.packed_bytes8(M, K)
+    frac = check_codes8(unpack_host8(q, M, K), s.cpu().numpy(), qo, so, f"g={g} M={M} K={K}")
     assert frac == 1.0
 
 
@@ -55,11 +57,12 @@ def test_rotquant8_closed_forms(cr):
     q, s = cr.convrot_prepare_weight8(to_dev_bf16(bits), g)
     torch.cuda.synchronize()
     qo, so = oracle.rotquant(bits, g, qmax=127)
-    assert np.array_equal(q.cpu().numpy(), qo) and np.array_equal(s.cpu().numpy(), so)
-    assert (q[1].cpu().numpy() == -127).all() and s[2].item() == 1.0 and not q[2].any()
+    q = unpack_host8(q, 4, K)
+    assert np.array_equal(q, qo) and np.array_equal(s.cpu().numpy(), so)
+    assert (q[1] == -127).all() and s[2].item() == 1.0 and not q[2].any()
 
 
-@pytest.mark.parametrize("M,N,K", [(256, 128, 64), (300, 520, 1024), (1, 1, 64), (33, 7, 192), (257, 513, 3072),
+@pytest.mark.parametrize("M,N,K", [(256, 128, 64), (300, 520, 1024), (1, 1, 64), (33, 7, 192), (257, 513, 3072), (35, 19, 96),
                                    (64, 1030, 12288), (513, 258, 128), (40, 136, 65536)])
 def test_gemm8_i32_bit_exact(cr, M, N, K):
     rng = np.random.default_rng(M * 5 + N * 3 + K)
@@ -67,7 +70,7 @@ def test_gemm8_i32_bit_exact(cr, M, N, K):
     qw = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
     qx[0, :] = 127
     qw[0, :] = -127           # reaches the accumulator bound 127^2 K
-    acc = cr.convrot_w8a8_gemm_i32(torch.from_numpy(qx).cuda(), torch.from_numpy(qw).cuda())
+    acc = cr.convrot_w8a8_gemm_i32(codes8_to_dev(qx), codes8_to_dev(qw), M, N, K)
     torch.cuda.synchronize()
     assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
 
@@ -80,8 +83,8 @@ def test_gemm8_dequant_on_identical_codes(cr, M, N, K, with_bias):
     sx = np.exp(rng.uniform(-6, 2, M)).astype(np.float32)
     sw = np.exp(rng.uniform(-9, -4, N)).astype(np.float32)
     bias = wl.f32_to_bf16_bits((rng.standard_normal(N) * 0.5).astype(np.float32)) if with_bias else None
-    y = cr.convrot_w8a8_gemm_dequant(torch.from_numpy(qx).cuda(), torch.from_numpy(sx).cuda(), torch.from_numpy(qw).cuda(),
-                                     torch.from_numpy(sw).cuda(), bias=None if bias is None else to_dev_bf16(bias))
+    y = cr.convrot_w8a8_gemm_dequant(codes8_to_dev(qx), torch.from_numpy(sx).cuda(), codes8_to_dev(qw),
+                                     torch.from_numpy(sw).cuda(), K, bias=None if bias is None else to_dev_bf16(bias))
     torch.cuda.synchronize()
     yb = bf16_to_host_bits(y)
     yo = oracle.dequant(oracle.int_gemm(qx, qw), sx, sw, bias)
@@ -100,7 +103,7 @@ def test_forward8_tiny_config(cr, g):
     wq, ws = cr.convrot_prepare_weight8(to_dev_bf16(w), g)
     y = cr.convlinear8bit_forward(to_dev_bf16(x), wq, ws, g, bias=to_dev_bf16(bias))
     xq, xs = cr.convrot_rotquant_act8(to_dev_bf16(x), g)
-    y2 = cr.convrot_w8a8_gemm_dequant(xq, xs, wq, ws, bias=to_dev_bf16(bias))
+    y2 = cr.convrot_w8a8_gemm_dequant(xq, xs, wq, ws, spec.K, bias=to_dev_bf16(bias))
     torch.cuda.synchronize()
     assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
     yo = oracle.convlinear(x, w, g, bias=bias, qmax=127)
@@ -122,11 +125,11 @@ def test_forward8_full_size_headline_shape(cr):
     torch.cuda.synchronize()
     qwo, swo = oracle.rotquant(w, spec.group, qmax=127)
     qxo, sxo = oracle.rotquant(x, spec.group, qmax=127)
-    assert check_codes8(wq.cpu().numpy(), ws.cpu().numpy(), qwo, swo, "W8") == 1.0
-    assert check_codes8(xq.cpu().numpy(), xs.cpu().numpy(), qxo, sxo, "X8") == 1.0
+    assert check_codes8(unpack_host8(wq, spec.N, spec.K), ws.cpu().numpy(), qwo, swo, "W8") == 1.0
+    assert check_codes8(unpack_host8(xq, spec.M, spec.K), xs.cpu().numpy(), qxo, sxo, "X8") == 1.0
     rows = np.array(sorted(set([0, 255, 256, spec.M - 1]) | set(np.random.default_rng(0).choice(spec.M, 24, replace=False).tolist())))
     rt = torch.from_numpy(rows).cuda()
-    acc = cr.convrot_w8a8_gemm_i32(xq[rt].contiguous(), wq)
+    acc = cr.convrot_w8a8_gemm_i32(codes8_to_dev(qxo[rows]), wq, len(rows), spec.N, spec.K)
     torch.cuda.synchronize()
     acc_o = oracle.int_gemm(qxo[rows], qwo)
     assert np.array_equal(acc.cpu().numpy(), acc_o)
@@ -136,8 +139,15 @@ def test_forward8_full_size_headline_shape(cr):
     check_output(bf16_to_host_bits(y[rt]), yo, "forward8 headline")
 
 
-def test_w8a8_rejects_k_not_multiple_of_64(cr):
-    x = torch.zeros((4, 96), dtype=torch.bfloat16, device="cuda")
+def test_w8a8_k_multiple_of_32_with_zero_padded_last_stage(cr):
+    # K = 96: one and a half 64-byte stages per row; the layout pads the second with zero codes
+    spec = wl.LayerSpec("w8_k96", M=35, K=96, N=19, group=16, seed=21)
+    x, w = wl.make_layer(spec)
+    wq, ws = cr.convrot_prepare_weight8(to_dev_bf16(w), 16)
+    y = cr.convlinear8bit_forward(to_dev_bf16(x), wq, ws, 16)
+    torch.cuda.synchronize()
+    check_output(bf16_to_host_bits(y), oracle.convlinear(x, w, 16, qmax=127), "forward8 K=96")
+    x48 = torch.zeros((4, 48), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(cr.ConvRotError) as e:
-        cr.convrot_rotquant_act8(x, 16)
+        cr.convrot_rotquant_act8(x48, 16)
     assert e.value.status == -2
