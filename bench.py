@@ -30,8 +30,8 @@ I8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published
 # dispatch), each scaled by what the same counter reads for a plain copy of known size (x2.0 and
 # x1.0); the runs are in profiles/gemm_w4a4_and_rotquant_headline_hbm_traffic_and_mfma_busy.md.
 # These are stored measurements of this build, not taken live (bench.py cannot run the profiler on itself).
-MEASURED_TRAFFIC_BYTES = {"gemm_w4a4_kernel": 78753 * 1024 * 2.0 + 110590 * 1024 * 1.0,
-                          "rotquant_kernel": 14065 * 1024 * 2.0 + 7031 * 1024 * 1.0}
+MEASURED_TRAFFIC_BYTES = {"gemm_w4a4_kernel": 82803 * 1024 * 2.0 + 110592 * 1024 * 1.0,
+                          "rotquant_kernel": 14070 * 1024 * 2.0 + 7012 * 1024 * 1.0}
 COPY_BYTES = 512 << 20       # size of the calibration copy (--calibrate-copy)
 COLD_FOOTPRINT = 768 << 20   # kernel A, cold: bytes touched between two uses of one buffer set
 
