@@ -4,6 +4,7 @@
 
 #include "convrot.h"
 #include "convrot_internal.h"
+#include "e2m3_layout.h"
 #include "panel_layout.h"
 
 namespace {
@@ -64,7 +65,7 @@ int convrot_version(void) { return CONVROT_VERSION; }
 size_t convrot_packed_bytes(int64_t rows, int64_t K)
 {
     if (rows < 0 || K <= 0 || (K & 1)) return 0;
-    return (size_t)convrot::panel::matrix_bytes(rows, K / 2);
+    return (size_t)convrot::e2m3::matrix_bytes(rows, K);
 }
 
 size_t convrot_packed_bytes8(int64_t rows, int64_t K)

@@ -33,6 +33,13 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
+// The same, and every LDS (and scalar memory) operation of the wavefront returned as well.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_lgkm0()
+{
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+}
+
 // global_load_lds_dwordx4: lane l copies 16 bytes from its global address to LDS address M0 + 16 l.
 __device__ __forceinline__ void lds_dma16(const uint8_t *base, uint32_t lane_off, uint32_t lds_addr)
 {

@@ -1,76 +1,70 @@
-// Kernel B of libconvrot: W4A4 GEMM on packed 4-bit codes with the dequantisation fused
+// Kernel B of libconvrot: W4A4 GEMM on 4-bit codes with the dequantisation fused
 // (ConvRot paper Sec. 4.3: 4-bit matrix multiplication, then dequantisation).
 //
-//   acc[m,n] = sum_k q_x[m,k] q_w[n,k]        int32, exact
-//   Y[m,n]   = bf16( float(acc) * s_x[m] * s_w[n] )
+//   acc[m,n] = sum_k q_x[m,k] q_w[n,k]        exact
+//   Y[m,n]   = bf16( float(acc) * s_x[m] * s_w[n] + bias[n] )
 //
-// gfx950 has no 4-bit integer MFMA, so the codes are widened on chip to int8 and fed to
-// v_mfma_i32_32x32x32_i8.  Widening keeps each nibble in the top half of its byte:
-//     hi = p & 0xF0F0F0F0            (codes 1,3,5,7 of a dword, each as 16*code)
-//     lo = (p << 4) & 0xF0F0F0F0     (codes 0,2,4,6, each as 16*code)
-// which needs no sign extension.  Both operands are widened the same way, so byte i of one
-// always meets byte i of the other (a dot product does not care in which order k is visited)
-// and every product is 256 * q_x * q_w.  The accumulator is therefore exactly 256 * acc
-// (|256 acc| <= 256 * 49 * K < 2^31 for K <= 65536) and the factor 2^-8 is folded, exactly,
-// into the epilogue.
+// gfx950 has no 4-bit integer MFMA, but every code in [-7, 7] is an FP6 (E2M3) number, and
+// v_mfma_f32_32x32x64_f8f6f4 on FP6 operands runs at twice the rate of the int8 MFMA.  Products of two
+// codes (|.| <= 49) and all their partial sums (|.| <= 49 K < 2^22 for K <= 65536) are integers that
+// fp32 holds exactly, so the fp32 accumulators carry the exact integer result whatever the order of
+// the additions.  The codes arrive from the rotate+quantise kernel already as FP6 (e2m3_layout.h), six
+// bits each, in the register image the MFMA wants: nothing is unpacked or widened here.  (On this
+// chip the int8 path is held back by power, not by issue: the same int8 kernel ran 98 us on all-zero
+// codes and 113-135 us on real ones, and a register-only loop sustains 2.7 POP/s of int8 MFMA against
+// 6.6 POP/s of FP6 MFMA on workload-like data.)
 //
-// Data movement.  A block owns a 256 x 128 output tile (4 wavefronts, 128 x 64 each, 128
-// accumulator registers per lane) and needs 256 registers per lane and 74 KB of LDS, so that two
-// blocks share a compute unit: while one runs its prologue or epilogue, or waits at a barrier,
-// the other keeps the MFMA pipe busy.  Packed codes travel HBM -> LDS with
-// global_load_lds_dwordx4 (no register staging) into a ring of 3 stages of 128 codes (64 bytes)
-// of K.  The operands sit in HBM as 1 KB panels of 16 rows x 64 bytes (panel_layout.h), so that one such
-// instruction - 16 tile rows of one stage - reads one contiguous kilobyte: the same bytes fetched as
-// sixteen 64-byte row pieces move at under half the rate and held the whole loop back.
-// The codes stay packed in LDS and are widened in registers after ds_read_b128, 3 VALU
-// operations per packed dword.  LDS rows are 64 bytes; the four 16-byte pieces of a row are
-// XOR-swizzled by row so that the fragment reads (32 consecutive rows, one piece) touch every
-// bank once.  The swizzle is applied on the global side: an LDS-direct load writes lane l at
-// base + 16 l, so lane l simply fetches the piece that belongs there.
+// Data movement.  A block owns a 256 x 128 output tile (4 wavefronts, 128 x 64 each, 128 accumulator
+// registers per lane) and needs 74 KB of LDS, so that two blocks share a compute unit: while one runs
+// its prologue or epilogue, or waits at a barrier, the other keeps the MFMA pipe busy.  The operands
+// sit in HBM as 3 KB blocks of 32 rows x 128 codes (an A plane of 32 x 64 bytes and a B plane of
+// 32 x 32 bytes, both XOR-swizzled for the fragment reads); a K128 stage of the tile is 12 such blocks
+// = 36 global_load_lds_dwordx4 of one contiguous kilobyte each, nine per wavefront, straight copies
+// into a ring of two stage buffers.  A fragment (32 rows x 64 codes, 24 bytes per lane) is one
+// ds_read_b128 from the A plane and one ds_read_b64 from the B plane and is an MFMA operand as read.
 //
 // The MFMA's row operand is the W tile and its column operand the X tile, so that a lane ends up
 // with four consecutive n for one m; the epilogue scales, rounds to bf16, transposes through LDS
 // and writes 16 bytes per lane, 128 contiguous bytes per output row.
-//
-// Any K the library accepts: the panel layout pads the last stage of a row with zero codes.
 #include "gemm_common.h"
 
 #include "convrot_internal.h"
-#include "panel_layout.h"
+#include "e2m3_layout.h"
 
 namespace convrot {
 
 using gemm::kNumXcd;
-using gemm::kRowBytes;
-using gemm::kSubSteps;
 using gemm::lds_dma16;
-using gemm::nib_hi;
-using gemm::nib_lo;
 using gemm::pack_bf16x2;
-using gemm::swz;
 using gemm::tile_of_block;
-using gemm::v16i;
 using gemm::v4i;
 using gemm::wait_vmcnt;
+using gemm::wait_vmcnt_lgkm0;
 
 namespace {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;                 // 4 wavefronts, 2 x 2
 constexpr int TM = 256, TN = 128;             // block tile
 constexpr int WM = 128, WN = 64;              // wavefront tile
 constexpr int XF = WM / 32, WF = WN / 32;     // fragments (32 rows x one K64 step) per wavefront: 4 of X, 2 of W
 constexpr int NF = XF + WF;
-constexpr int kStages = 3;
-constexpr int kStageBytes = (TM + TN) * kRowBytes;        // 24 KB
-constexpr int kRingBytes = kStages * kStageBytes;         // 72 KB
-constexpr int kChunks = kStageBytes / 1024 / 4;           // 1 KB LDS-direct loads per wavefront per stage: 6
-constexpr int kXChunks = TM * kRowBytes / 1024 / 4;       // ... of which the first 4 fetch X rows
-constexpr int kEpiPitch = WN * 2 + 16;                    // bf16 row of the wavefront tile + pad
-constexpr int kLdsTotal = kRingBytes + (TM + 2 * TN) * 4; // + the tile's dequantisation scales and bias
-static_assert(kChunks * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
+constexpr int kTileBlocks = (TM + TN) / e2m3::kRows;             // 32-row blocks of a stage: 8 of X, then 4 of W
+constexpr int kAPlane = (TM + TN) * e2m3::kARowBytes;            // LDS stage: A parts, tile row r at r * 64 ... 24 KB
+constexpr int kBPlane = (TM + TN) * e2m3::kBRowBytes;            // ... then B parts, tile row r at r * 32: 12 KB
+constexpr int kStageBytes = kAPlane + kBPlane;                   // 36 KB
+constexpr int kStages = 2;
+constexpr int kRingBytes = kStages * kStageBytes;                // 72 KB
+constexpr int kLoads = kStageBytes / 1024 / 4;                   // 1 KB LDS-direct loads per wavefront per stage: 9
+constexpr int kEpiPitch = WN * 2 + 16;                           // bf16 row of the wavefront tile + pad
+constexpr int kLdsTotal = kRingBytes + (TM + 2 * TN) * 4;        // + the tile's dequantisation scales and bias
+static_assert(kLoads * 4 * 1024 == kStageBytes && kTileBlocks * 3 == kLoads * 4, "stage must split into 1 KB loads over 4 wavefronts");
 static_assert(4 * 32 * kEpiPitch <= kRingBytes, "epilogue staging must fit the ring");
 static_assert(2 * kLdsTotal <= 160 * 1024, "two blocks per compute unit");
-static_assert(kSubSteps == 2 && NF == 6, "slot plan of a K64 step");
+static_assert(NF == 6 && kLoads == 9, "slot plan of a K64 step");
 
 }  // namespace
 
@@ -88,7 +82,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     const int m0 = tm * TM, n0 = tn * TN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
-    const int KT = (int)panel::k_panels(K >> 1);   // stages = K-panels per row; the last one is zero-padded
+    const int KS = (int)e2m3::stages(K);   // K128 stages per row; the last one is zero-padded
+
     // ---- dequantisation scales of the tile's rows and columns: thread t fetches x_scale[m0 + t] and
     // w_scale[n0 + t] now, so that the latency hides under the main loop, and parks them in LDS (past
     // the ring) once the loop is over.
@@ -101,142 +96,124 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
         }
     }
 
-    // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
-    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..383 are W), which is one 1 KB panel of the operand
-    // (panel_layout.h), K-panels of the same rows 1 KB apart; lane l fills slot l & 3 of row l >> 2.
-    const uint8_t *xtile = Xq + (int64_t)(m0 / panel::kRows) * KT * panel::kBytes;
-    const uint8_t *wtile = Wq + (int64_t)(n0 / panel::kRows) * KT * panel::kBytes;
-    uint32_t goff[kChunks];   // byte offset of this lane's piece inside the operand's tile rows, stage 0
+    // ---- global -> LDS (direct).  Load j of a stage (0..35) copies kilobyte j % 3 of the 3 KB block of
+    // 32-row group j / 3 of the tile (groups 0..7 are X rows, 8..11 W rows): kilobytes 0, 1 are the A plane
+    // (rows 0-15, 16-31), kilobyte 2 the B plane.  Wavefront w issues loads w, w + 4, ...; a group past
+    // the operand's last one (edge tiles) re-reads the last one, whose results are never stored.
+    const int x_groups = (M + e2m3::kRows - 1) / e2m3::kRows, w_groups = (N + e2m3::kRows - 1) / e2m3::kRows;
+    const uint8_t *src[kLoads];   // stage 0 source of each of this wavefront's loads (wavefront-uniform)
+    uint32_t dst[kLoads];         // its place in a stage buffer
 #pragma unroll
-    for (int i = 0; i < kChunks; ++i) {
-        const int row_t = 16 * (wave + 4 * i) + lane / 4;
-        const int piece = (lane % 4) ^ swz(row_t);
-        const int r = i < kXChunks ? min(row_t, M - 1 - m0) : min(row_t - TM, N - 1 - n0);   // edge rows re-read the last valid row
-        goff[i] = (uint32_t)(r / panel::kRows) * (uint32_t)KT * panel::kBytes + (r % panel::kRows) * kRowBytes + piece * 16;
+    for (int i = 0; i < kLoads; ++i) {
+        const int j = __builtin_amdgcn_readfirstlane(wave) + 4 * i, grp = j / 3, part = j % 3;
+        const bool is_x = grp < TM / e2m3::kRows;
+        const int g = is_x ? min(m0 / e2m3::kRows + grp, x_groups - 1) : min(n0 / e2m3::kRows + grp - TM / e2m3::kRows, w_groups - 1);
+        src[i] = (is_x ? Xq : Wq) + (int64_t)g * KS * e2m3::kBlockBytes + part * 1024;
+        dst[i] = part < 2 ? grp * e2m3::kAPlaneBytes + part * 1024 : kAPlane + grp * e2m3::kBPlaneBytes;
     }
     // LDS-direct loads are issued from inline assembly so that the compiler does not serialise every
     // later LDS read behind them; completion is tracked by hand with vmcnt.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
-    const uint32_t wave_lds = lds_base + __builtin_amdgcn_readfirstlane(wave) * 1024;
-    // chunk i of this wavefront's share of stage kt; chunk wave + 4 i sits 4096 i further on
-    auto load_chunk = [&](int kt, int i) {
-        const uint32_t sl = wave_lds + ((unsigned)kt % kStages) * kStageBytes;
-        lds_dma16((i < kXChunks ? xtile : wtile) + (uint32_t)kt * panel::kBytes, goff[i], sl + i * 4096);
+    const uint32_t lane16 = lane * 16;
+    auto load_stage_part = [&](int s, auto IC) {   // load i of this wavefront's share of stage s
+        constexpr int i = decltype(IC)::value;
+        lds_dma16(src[i], lane16 + (uint32_t)s * e2m3::kBlockBytes, lds_base + ((unsigned)s % kStages) * kStageBytes + dst[i]);
     };
 
-    // ---- LDS -> registers: fragment of 32 rows x 32 packed codes per lane-half
+    // ---- LDS -> registers: a fragment is 32 rows x one K64 step; lane l holds chunk 2 ks + l / 32 of row l % 32
     const int frow = lane & 31;
-    const int fswz = swz(frow);                              // tile rows differ from frow by multiples of 32
-    int foff[kSubSteps];                                     // per K64 step: byte offset inside a 32-row slab
+    int offa[2], offb[2];     // per K64 step: byte offsets of the lane's A part and B part inside a 32-row group
 #pragma unroll
-    for (int ks = 0; ks < kSubSteps; ++ks) foff[ks] = frow * kRowBytes + (((2 * ks + (lane >> 5)) ^ fswz) << 4);
-    const int xslab = wm0 * kRowBytes;
-    const int wslab = (TM + wn0) * kRowBytes;
+    for (int ks = 0; ks < 2; ++ks) {
+        const int c = 2 * ks + (lane >> 5);
+        offa[ks] = frow * e2m3::kARowBytes + ((c ^ e2m3::swz_a(frow)) << 4);
+        offb[ks] = kAPlane + frow * e2m3::kBRowBytes + ((c ^ e2m3::swz_b(frow)) << 3);
+    }
+    const int xrow0 = wm0, wrow0 = TM + wn0;   // first tile row of the wavefront's X and W fragments
 
-    uint4 raw[NF];   // packed fragments of one K64 step: 0..3 X rows 32 f .., 4..5 W rows 32 (f - 4) ..
-    auto read_frag = [&](int kt, int ks, auto F) {
-        constexpr int f = decltype(F)::value;
-        const uint8_t *sbase = lds + ((unsigned)kt % kStages) * kStageBytes + foff[ks];
-        if constexpr (f < XF) raw[f] = *reinterpret_cast<const uint4 *>(sbase + xslab + f * 32 * kRowBytes);
-        else raw[f] = *reinterpret_cast<const uint4 *>(sbase + wslab + (f - XF) * 32 * kRowBytes);
+    v8i op[2][NF];   // [K64 step parity][fragment]: 0..3 X rows 32 f .., 4..5 W rows 32 (f - 4) ..; 6 dwords used
+    auto read_frag = [&](int s, auto KSI, auto F) {
+        constexpr int ks = decltype(KSI)::value, f = decltype(F)::value;
+        const uint8_t *sbase = lds + ((unsigned)s % kStages) * kStageBytes;
+        const int row0 = f < XF ? xrow0 + f * 32 : wrow0 + (f - XF) * 32;
+        const v4i a = *reinterpret_cast<const v4i *>(sbase + offa[ks] + row0 * e2m3::kARowBytes);
+        const v2i b = *reinterpret_cast<const v2i *>(sbase + offb[ks] + row0 * e2m3::kBRowBytes);
+        v8i o = __builtin_shufflevector(a, a, 0, 1, 2, 3, -1, -1, -1, -1);
+        o[4] = b.x;
+        o[5] = b.y;
+        op[ks][f] = o;
     };
 
-    v16i acc[XF][WF];
+    v16f acc[XF][WF];
 #pragma unroll
     for (int i = 0; i < XF; ++i)
 #pragma unroll
         for (int j = 0; j < WF; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // A K64 step is two MFMAs per accumulator tile: half 0 on the first two dwords of every fragment,
-    // half 1 on the last two.  op[h][f] holds the widened dwords 2h, 2h+1 of fragment f.  The two halves
-    // leapfrog: while the 8 MFMAs of half 0 run, half 1 of the same step is widened and the fragment
-    // registers, now spent, are refilled from LDS with the next step; while half 1 runs, half 0 of
-    // the next step is widened into the registers half 0 has just released.
-    v4i op[2][NF];
-    auto widen_dword = [&](auto H, auto F, auto C) {   // dword 2 H + C of fragment F
-        constexpr int h = decltype(H)::value, f = decltype(F)::value, c = decltype(C)::value, d = 2 * h + c;
-        const uint32_t p = d == 0 ? raw[f].x : d == 1 ? raw[f].y : d == 2 ? raw[f].z : raw[f].w;
-        op[h][f][2 * c] = (int)nib_lo(p);
-        op[h][f][2 * c + 1] = (int)nib_hi(p);
-    };
-
-    // One K64 step, slot by slot, in issue order (scheduling barriers pin it).  A wavefront issues in
+    // One K64 step, slot by slot, in issue order (scheduling barriers pin it): a wavefront issues in
     // order, so every memory instruction gets an MFMA slot of its own instead of queueing up in a burst.
-    //   half 0, slot m:  MFMA (i = m % 4, j = m / 4) on op[0];  m < 6: widen half 1 of fragment m, then
-    //                    fetch fragment m of the next step (stage nkt, K64 step nks) over it
-    //   half 1, slot m:  MFMA on op[1];  widen dwords [3m/2, 3(m+1)/2) of the 12 half-0 dwords of the next
-    //                    step;  REFILL, m < 6: LDS-direct load of chunk m of stage rkt
-    auto half0_slot = [&](auto MI, int nkt, int nks) {
-        constexpr int m = decltype(MI)::value, i = m % 4, j = m / 4;
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(op[0][XF + j], op[0][i], acc[i][j], 0, 0, 0);
-        if constexpr (m < NF) {
-            widen_dword(std::integral_constant<int, 1>{}, std::integral_constant<int, m>{}, std::integral_constant<int, 0>{});
-            widen_dword(std::integral_constant<int, 1>{}, std::integral_constant<int, m>{}, std::integral_constant<int, 1>{});
-            read_frag(nkt, nks, std::integral_constant<int, m>{});
+    //   slot m: MFMA (i = m % 4, j = m / 4) on the fragments of step KSI;  m < 6: fetch fragment m of the
+    //   next step (stage ns, the other K64 parity);  REFILL: LDS-direct loads m (and 8 in slot 0) of stage rs
+    auto slot = [&](auto MI, auto KSI, auto REFILL, int ns, int rs) {
+        constexpr int m = decltype(MI)::value, ks = decltype(KSI)::value, i = m % 4, j = m / 4;
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(op[ks][XF + j], op[ks][i], acc[i][j], 2, 2, 0, 0, 0, 0);
+        if constexpr (decltype(REFILL)::value) {
+            load_stage_part(rs, std::integral_constant<int, m>{});
+            if constexpr (m == 0) load_stage_part(rs, std::integral_constant<int, 8>{});
         }
+        if constexpr (m < NF) read_frag(ns, std::integral_constant<int, 1 - ks>{}, std::integral_constant<int, m>{});
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto half1_slot = [&](auto MI, auto REFILL, int rkt) {
-        constexpr int m = decltype(MI)::value, i = m % 4, j = m / 4;
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(op[1][XF + j], op[1][i], acc[i][j], 0, 0, 0);
-        if constexpr (decltype(REFILL)::value && m < kChunks) load_chunk(rkt, m);
-        constexpr int lo = 3 * m / 2, hi = 3 * (m + 1) / 2;   // 12 dwords over 8 slots
-        if constexpr (lo < hi)
-            widen_dword(std::integral_constant<int, 0>{}, std::integral_constant<int, lo / 2>{}, std::integral_constant<int, lo % 2>{});
-        if constexpr (lo + 1 < hi)
-            widen_dword(std::integral_constant<int, 0>{}, std::integral_constant<int, (lo + 1) / 2>{}, std::integral_constant<int, (lo + 1) % 2>{});
+    auto step = [&](auto KSI, auto REFILL, int ns, int rs) {
         __builtin_amdgcn_sched_barrier(0);
+#define CONVROT_SLOT(m) slot(std::integral_constant<int, m>{}, KSI, REFILL, ns, rs);
+        CONVROT_SLOT(0) CONVROT_SLOT(1) CONVROT_SLOT(2) CONVROT_SLOT(3) CONVROT_SLOT(4) CONVROT_SLOT(5) CONVROT_SLOT(6) CONVROT_SLOT(7)
+#undef CONVROT_SLOT
     };
-    // With SYNC the step opens with the wait for stage nkt (all of this wavefront's loads: with a ring
-    // of three only that stage is in flight) and the block barrier that extends it to everybody's share.
-    auto step = [&](auto SYNC, auto REFILL, int nkt, int nks, int rkt) {
+    // The block meets once per stage, between its two K64 steps: every wavefront has then read all of
+    // stage s into registers (its own LDS reads have returned), so the buffer can take stage s + 2, and
+    // its share of stage s + 1 has landed, which the barrier extends to everybody's share.
+    auto meet = [&]() {
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (decltype(SYNC)::value) {
-            wait_vmcnt<0>();
-            __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#define CONVROT_H0(m) half0_slot(std::integral_constant<int, m>{}, nkt, nks);
-        CONVROT_H0(0) CONVROT_H0(1) CONVROT_H0(2) CONVROT_H0(3) CONVROT_H0(4) CONVROT_H0(5) CONVROT_H0(6) CONVROT_H0(7)
-#undef CONVROT_H0
-#define CONVROT_H1(m) half1_slot(std::integral_constant<int, m>{}, REFILL, rkt);
-        CONVROT_H1(0) CONVROT_H1(1) CONVROT_H1(2) CONVROT_H1(3) CONVROT_H1(4) CONVROT_H1(5) CONVROT_H1(6) CONVROT_H1(7)
-#undef CONVROT_H1
+        wait_vmcnt_lgkm0<0>();
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- pipeline: stages 0 and 1 in flight; when stage 0 has landed its first fragments are fetched
-    // and their half 0 widened.  The block meets once per stage, at the start of the stage's second
-    // K64 step: stage kt+1 must have landed by then (its first fragments are fetched during that
-    // step), and the buffer stage kt-1 vacated is refilled with stage kt+2.  The last two stages
-    // refill nothing (what they fetch past the last stage is a ring buffer whose contents are unused).
-#pragma unroll
-    for (int i = 0; i < kChunks; ++i) load_chunk(0, i);
-    if (KT > 1) {
-#pragma unroll
-        for (int i = 0; i < kChunks; ++i) load_chunk(1, i);
-        wait_vmcnt<kChunks>();
+    // ---- pipeline: stages 0 and 1 in flight; when stage 0 has landed its first fragments are fetched.
+    using K0 = std::integral_constant<int, 0>;
+    using K1 = std::integral_constant<int, 1>;
+#define CONVROT_ALL_LOADS(s) \
+    load_stage_part(s, std::integral_constant<int, 0>{}); load_stage_part(s, std::integral_constant<int, 1>{}); \
+    load_stage_part(s, std::integral_constant<int, 2>{}); load_stage_part(s, std::integral_constant<int, 3>{}); \
+    load_stage_part(s, std::integral_constant<int, 4>{}); load_stage_part(s, std::integral_constant<int, 5>{}); \
+    load_stage_part(s, std::integral_constant<int, 6>{}); load_stage_part(s, std::integral_constant<int, 7>{}); \
+    load_stage_part(s, std::integral_constant<int, 8>{});
+    CONVROT_ALL_LOADS(0)
+    if (KS > 1) {
+        CONVROT_ALL_LOADS(1)
+        wait_vmcnt<kLoads>();
     } else {
         wait_vmcnt<0>();
     }
+#undef CONVROT_ALL_LOADS
     __syncthreads();
-#define CONVROT_F(f) read_frag(0, 0, std::integral_constant<int, f>{});
+#define CONVROT_F(f) read_frag(0, K0{}, std::integral_constant<int, f>{});
     CONVROT_F(0) CONVROT_F(1) CONVROT_F(2) CONVROT_F(3) CONVROT_F(4) CONVROT_F(5)
 #undef CONVROT_F
-#define CONVROT_W(f) widen_dword(std::integral_constant<int, 0>{}, std::integral_constant<int, f>{}, std::integral_constant<int, 0>{}); \
-                     widen_dword(std::integral_constant<int, 0>{}, std::integral_constant<int, f>{}, std::integral_constant<int, 1>{});
-    CONVROT_W(0) CONVROT_W(1) CONVROT_W(2) CONVROT_W(3) CONVROT_W(4) CONVROT_W(5)
-#undef CONVROT_W
 
-    int kt = 0;
-    for (; kt < KT - 2; ++kt) {
-        step(std::false_type{}, std::false_type{}, kt, 1, 0);
-        step(std::true_type{}, std::true_type{}, kt + 1, 0, kt + 2);
+    int s = 0;
+    for (; s < KS - 2; ++s) {
+        step(K0{}, std::false_type{}, s, 0);          // first K64 step of stage s; fetches the fragments of the second
+        meet();
+        step(K1{}, std::true_type{}, s + 1, s + 2);   // second step; fetches the first fragments of stage s + 1; refill
     }
-    for (; kt < KT; ++kt) {
-        step(std::false_type{}, std::false_type{}, kt, 1, 0);
-        step(std::true_type{}, std::false_type{}, kt + 1, 0, 0);
+    for (; s < KS; ++s) {   // the last two stages refill nothing (what the very last step fetches is unused)
+        step(K0{}, std::false_type{}, s, 0);
+        meet();
+        step(K1{}, std::false_type{}, s + 1, 0);
     }
 
     // ---- epilogue.  Lane l, register r of a 32x32 accumulator tile: m = l % 32, n = 8 (r/4) + 4 (l/32) + r % 4.
@@ -254,7 +231,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
                     if (n >= N) continue;
                     int32_t o[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = acc[i][j][rb * 4 + e] >> 8;
+                    for (int e = 0; e < 4; ++e) o[e] = (int32_t)acc[i][j][rb * 4 + e];   // exact: an integer below 2^24
                     int32_t *dst = acc_out + (int64_t)m * N + n;
                     if (vec_ok) {
                         *reinterpret_cast<int4 *>(dst) = make_int4(o[0], o[1], o[2], o[3]);
@@ -268,7 +245,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
         }
     } else {
         float *sx_lds = reinterpret_cast<float *>(lds + kRingBytes), *sw_lds = sx_lds + TM;
-        sx_lds[tid] = my_sx * 0.00390625f;   // 2^-8 undoes the 16 * 16 of the widening
+        sx_lds[tid] = my_sx;
         if (tid < TN) {
             sw_lds[tid] = my_sw;
             sw_lds[TN + tid] = my_b;
@@ -300,7 +277,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
                         float y[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            y[e] = ((float)acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
+                            y[e] = (acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
                             if constexpr (decltype(BIAS)::value) y[e] += sw_lds[TN + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4 + e];
                         }
                         const int col = j * 32 + rb * 8 + (lane >> 5) * 4;

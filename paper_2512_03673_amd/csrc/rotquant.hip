@@ -28,6 +28,7 @@
 #include <stdint.h>
 
 #include "convrot_internal.h"
+#include "e2m3_layout.h"
 #include "panel_layout.h"
 
 namespace convrot {
@@ -38,6 +39,8 @@ constexpr int kUnit = 16;  // elements per unit
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int v6u __attribute__((ext_vector_type(6)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x)
@@ -119,9 +122,10 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
     // Blocks are dealt round-robin to the 8 XCDs, each with an L2 of its own.  The 16 rows of an output
     // panel go to consecutive blocks of one XCD, so that the 64-byte row pieces of a panel meet in one
     // L2 and leave it as whole lines.
-    const int bpp = panel::kRows / rows_per_block;            // blocks per row panel
+    constexpr int kGroupRows = BITS == 4 ? e2m3::kRows : panel::kRows;   // rows that share an output block
+    const int bpp = kGroupRows / rows_per_block;              // thread blocks per group of rows
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    const int64_t row = ((int64_t)(idx / bpp) * 8 + xcd) * panel::kRows + (idx % bpp) * rows_per_block + rib;
+    const int64_t row = ((int64_t)(idx / bpp) * 8 + xcd) * kGroupRows + (idx % bpp) * rows_per_block + rib;
     const bool row_ok = row < rows;
     const int units = K / kUnit;
 
@@ -181,81 +185,137 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
     // r approximates 1 / su to 2^-24, so z / su lies strictly between z * r_lo and z * r_hi
     // (r_lo, r_hi = r (1 -+ 2^-21)); rounding to an integer is monotonic, hence when both products
     // round to the same integer so does the exact quotient.  One fused multiply-add against
-    // 1.5 * 2^23 + 8 rounds a product to nearest, ties to even, and leaves q + 8 (1..15, so no borrow
-    // out of the nibble) in the low mantissa bits.  A wavefront in which any pair disagrees (a few
-    // in a thousand on random data; every exact tie, which bf16-grid inputs do produce when the
-    // scale is a short dyadic number) redoes its codes through the exact residual
-    // e = z - q su (one rounding of a quantity that is representable whenever q is the nearest or
-    // a neighbouring integer), which decides the rounding, ties to even, without a division.
-    // (BITS = 8: the same with q + 128 in the low byte, four codes per dword, Horner in base 256.)
-    constexpr uint32_t kOff = BITS == 4 ? 8u : 128u;          // offset that keeps every digit positive
-    constexpr int kDigit = BITS;                               // bits per code
-    constexpr int kPerDword = 32 / BITS;
-    constexpr int kDwords = kUnit / kPerDword;                 // output dwords per unit: 2 or 4
-    constexpr float kMagic = 12582912.0f + (float)kOff;
-    constexpr uint32_t kC = 0x4B400000u;                       // bits of 1.5 * 2^23
-    constexpr uint32_t kFlip = BITS == 4 ? 0x88888888u : 0x80808080u;   // offset-binary digits -> two's complement
-    constexpr uint32_t kDigitMask = (1u << BITS) - 1u;
-    // sum_e C 2^(BITS e) mod 2^32: only the first terms survive
-    constexpr uint32_t kBias = BITS == 4 ? kC + (kC << 4) + (kC << 8) : kC + (kC << 8);
+    // 1.5 * 2^23 (+ an offset) rounds a product to nearest, ties to even, and leaves the integer in
+    // the low mantissa bits.  A wavefront in which any pair disagrees (a few in a thousand on random
+    // data; every exact tie, which bf16-grid inputs do produce when the scale is a short dyadic
+    // number) redoes its codes through the exact residual e = z - q su (one rounding of a quantity
+    // that is representable whenever q is the nearest or a neighbouring integer), which decides the
+    // rounding, ties to even, without a division.
     const float su = s / norm;                                      // scale in un-normalised units (exact)
     const float r_lo = r * (1.0f - 0x1p-21f), r_hi = r * (1.0f + 0x1p-21f);
     const float half_su = 0.5f * su;
     const int tf = t ^ lane_flip_mask<G>();
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-        uint32_t disagree = 0;
-        uint32_t code[kDwords];
-#pragma unroll
-        for (int w = 0; w < kDwords; ++w) {
-            // Horner over the raw float bits: sum_e (C + u_e) 2^(BITS e) mod 2^32, C the magic's bits
-            // (the same sum over the other bracket: digits differ by at most one, so the two sums are
-            // equal exactly when every pair of codes is)
-            uint32_t acc = 0, acc_hi = 0;
-#pragma unroll
-            for (int e = kPerDword - 1; e >= 0; --e) {
-                const float z = v[i][kPerDword * w + e];
-                acc = (acc << kDigit) + __float_as_uint(fmaf(z, r_lo, kMagic));
-                acc_hi = (acc_hi << kDigit) + __float_as_uint(fmaf(z, r_hi, kMagic));
+    auto exact_code = [&](float z) {   // rne(z / su) as a float, from the exact residual
+        float q = rintf(z * r);
+        const float res = fmaf(-q, su, z);
+        const bool odd = ((int)q & 1) != 0;
+        const bool up = res > half_su || (res == half_su && odd);
+        const bool dn = res < -half_su || (res == -half_su && odd);
+        return q + ((up ? 1.0f : 0.0f) - (dn ? 1.0f : 0.0f));
+    };
+
+    if constexpr (BITS == 4) {
+        // 4-bit codes leave as FP6 (E2M3) numbers, the operand format of the GEMM's MFMA: every integer in
+        // [-7, 7] is one.  v_cvt_scalef32_2xpk16_fp6_f32 packs 2 x 16 floats into 6 dwords, interleaving
+        // its two sources (a0 b0 a1 b1 ...): fed (unit[0..7], next unit[0..7]) and (unit[8..15], next
+        // unit[8..15]) it returns this unit's 16 codes in dwords 0-2 and the next unit's in dwords 3-5.
+        // The order of the codes inside a unit does not matter to the GEMM as long as it is the same for
+        // activations and weights, which it is.
+        constexpr float kMagic = 12582912.0f;                       // 1.5 * 2^23
+        const int padded_units = (units + e2m3::kUnitsPerStage - 1) / e2m3::kUnitsPerStage * e2m3::kUnitsPerStage;
+        const int64_t stages = padded_units / e2m3::kUnitsPerStage;
+        uint8_t *const row_block = Xq + (row / e2m3::kRows) * stages * e2m3::kBlockBytes;
+        const int r32 = (int)(row % e2m3::kRows);
+        auto store_unit = [&](int i, uint32_t w0, uint32_t w1, uint32_t w2) {
+            // A 24-byte chunk (the 32 codes one MFMA lane consumes) is an even unit followed by the odd
+            // unit next to it, which the neighbouring lane holds: its first 16 bytes go to the A plane of the
+            // block, the other 8 to the B plane (e2m3_layout.h).  The even lane fetches the odd lane's first dword.
+            const uint32_t nb0 = __builtin_amdgcn_update_dpp(0u, w0, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+            const int unit = i * T + tf;
+            if (!(row_ok && unit < padded_units)) return;
+            uint32_t nb = nb0;
+            if (unit >= units) w0 = w1 = w2 = nb = 0;               // K padding: zero codes (units come in pairs: K % 32 == 0)
+            uint8_t *blk = row_block + (int64_t)(unit / e2m3::kUnitsPerStage) * e2m3::kBlockBytes;
+            const int c = (unit % e2m3::kUnitsPerStage) >> 1;       // chunk of the K128 stage
+            if ((unit & 1) == 0) {
+                *reinterpret_cast<u32x4 *>(blk + e2m3::a_offset(r32, c)) = u32x4{w0, w1, w2, nb};
+            } else {
+                *reinterpret_cast<u32x2 *>(blk + e2m3::b_offset(r32, c)) = u32x2{w1, w2};
             }
-            disagree |= acc ^ acc_hi;
-            code[w] = (acc - kBias) ^ kFlip;
+        };
+#pragma unroll
+        for (int i = 0; i < U; i += 2) {
+            const bool pair = i + 1 < U;
+            const int i1 = pair ? i + 1 : i;
+            uint32_t disagree = 0;
+            v16f qa, qb;    // conversion sources
+#pragma unroll
+            for (int e = 0; e < kUnit; ++e) {
+                const float lo0 = fmaf(v[i][e], r_lo, kMagic), hi0 = fmaf(v[i][e], r_hi, kMagic);
+                disagree |= __float_as_uint(lo0) ^ __float_as_uint(hi0);
+                float q1 = 0.0f;
+                if (pair) {
+                    const float lo1 = fmaf(v[i1][e], r_lo, kMagic), hi1 = fmaf(v[i1][e], r_hi, kMagic);
+                    disagree |= __float_as_uint(lo1) ^ __float_as_uint(hi1);
+                    q1 = lo1 - kMagic;
+                }
+                if (e < 8) { qa[e] = lo0 - kMagic; qa[8 + e] = q1; }
+                else { qb[e - 8] = lo0 - kMagic; qb[e] = q1; }
+            }
+            if (__builtin_amdgcn_ballot_w64(disagree != 0) != 0) {   // wavefront-uniform, rare
+#pragma unroll
+                for (int e = 0; e < kUnit; ++e) {
+                    const float q0 = exact_code(v[i][e]);
+                    const float q1 = pair ? exact_code(v[i1][e]) : 0.0f;
+                    if (e < 8) { qa[e] = q0; qa[8 + e] = q1; }
+                    else { qb[e - 8] = q0; qb[e] = q1; }
+                }
+            }
+            const v6u packed = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qa, qb, 1.0f);
+            store_unit(i, packed[0], packed[1], packed[2]);
+            if (pair) store_unit(i + 1, packed[3], packed[4], packed[5]);
         }
-        if (__builtin_amdgcn_ballot_w64(disagree != 0) != 0) {   // wavefront-uniform, rare
+    } else {
+        // 8-bit codes: q + 128 in the low byte of the rounded sum, four codes per dword by a Horner sum over
+        // the raw float bits, sum_e (C + u_e) 2^(8 e) mod 2^32 with C the magic's bits (the same sum over the
+        // other bracket: digits differ by at most one, so the two sums are equal exactly when every pair of
+        // codes is).
+        constexpr uint32_t kOff = 128u;                            // offset that keeps every digit positive
+        constexpr int kPerDword = 4;
+        constexpr int kDwords = kUnit / kPerDword;                 // output dwords per unit
+        constexpr float kMagic = 12582912.0f + (float)kOff;
+        constexpr uint32_t kC = 0x4B400000u;                       // bits of 1.5 * 2^23
+        constexpr uint32_t kFlip = 0x80808080u;                    // offset-binary digits -> two's complement
+        constexpr uint32_t kBias = kC + (kC << 8);                 // sum_e C 2^(8 e) mod 2^32: only the first terms survive
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            uint32_t disagree = 0;
+            uint32_t code[kDwords];
 #pragma unroll
             for (int w = 0; w < kDwords; ++w) {
-                uint32_t d = 0;
+                uint32_t acc = 0, acc_hi = 0;
 #pragma unroll
-                for (int e = 0; e < kPerDword; ++e) {
+                for (int e = kPerDword - 1; e >= 0; --e) {
                     const float z = v[i][kPerDword * w + e];
-                    float q = rintf(z * r);
-                    const float res = fmaf(-q, su, z);
-                    const bool odd = ((int)q & 1) != 0;
-                    const bool up = res > half_su || (res == half_su && odd);
-                    const bool dn = res < -half_su || (res == -half_su && odd);
-                    q += (up ? 1.0f : 0.0f) - (dn ? 1.0f : 0.0f);
-                    d |= ((uint32_t)(int)q & kDigitMask) << (kDigit * e);
+                    acc = (acc << 8) + __float_as_uint(fmaf(z, r_lo, kMagic));
+                    acc_hi = (acc_hi << 8) + __float_as_uint(fmaf(z, r_hi, kMagic));
                 }
-                code[w] = d;
+                disagree |= acc ^ acc_hi;
+                code[w] = (acc - kBias) ^ kFlip;
             }
-        }
-        // Panel layout: 1 KB panels of 16 rows x 64 bytes.  A unit is 8 bytes (4-bit) or 16 bytes (8-bit)
-        // of its row; units past the row's end inside its last K-panel are stored as zero codes.
-        const int unit = i * T + tf;
-        constexpr int kUnitBytes = kUnit * BITS / 8;
-        constexpr int kUnitsPerPanelRow = panel::kRowBytes / kUnitBytes;
-        const int padded_units = (units + kUnitsPerPanelRow - 1) / kUnitsPerPanelRow * kUnitsPerPanelRow;
-        if (row_ok && unit < padded_units) {
-            if (unit >= units) {
+            if (__builtin_amdgcn_ballot_w64(disagree != 0) != 0) {   // wavefront-uniform, rare
 #pragma unroll
-                for (int w = 0; w < kDwords; ++w) code[w] = 0;
+                for (int w = 0; w < kDwords; ++w) {
+                    uint32_t d = 0;
+#pragma unroll
+                    for (int e = 0; e < kPerDword; ++e)
+                        d |= ((uint32_t)(int)exact_code(v[i][kPerDword * w + e]) & 0xFFu) << (8 * e);
+                    code[w] = d;
+                }
             }
-            uint8_t *o = Xq + ((row >> 4) * (int64_t)(padded_units / kUnitsPerPanelRow) + unit / kUnitsPerPanelRow) * panel::kBytes +
-                         (int)(row & 15) * panel::kRowBytes + (unit % kUnitsPerPanelRow) * kUnitBytes;
-            // plain (cacheable) stores: the pieces of a line are merged in L2
-            if constexpr (BITS == 4) {
-                *reinterpret_cast<u32x2 *>(o) = u32x2{code[0], code[1]};
-            } else {
+            // Panel layout: 1 KB panels of 16 rows x 64 bytes, a unit is 16 bytes of its row; units past the
+            // row's end inside its last K-panel are stored as zero codes.
+            const int unit = i * T + tf;
+            constexpr int kUnitsPerPanelRow = panel::kRowBytes / kUnit;
+            const int padded_units = (units + kUnitsPerPanelRow - 1) / kUnitsPerPanelRow * kUnitsPerPanelRow;
+            if (row_ok && unit < padded_units) {
+                if (unit >= units) {
+#pragma unroll
+                    for (int w = 0; w < kDwords; ++w) code[w] = 0;
+                }
+                uint8_t *o = Xq + ((row >> 4) * (int64_t)(padded_units / kUnitsPerPanelRow) + unit / kUnitsPerPanelRow) * panel::kBytes +
+                             (int)(row & 15) * panel::kRowBytes + (unit % kUnitsPerPanelRow) * kUnit;
+                // plain (cacheable) stores: the pieces of a line are merged in L2
                 *reinterpret_cast<u32x4 *>(o) = u32x4{code[0], code[1], code[2], code[3]};
             }
         }
@@ -338,7 +398,8 @@ hipError_t launch_gu(const void *X, int64_t rows, int K, int waves_per_row, void
 {
     const int T = 64 * waves_per_row;
     // grid: 8 XCDs x whole row panels per XCD x blocks per panel (see the row mapping in the kernel)
-    auto grid_for = [&](int rpb) { return (unsigned)(((rows + 127) / 128) * 8 * (panel::kRows / rpb)); };
+    constexpr int kGroupRows = BITS == 4 ? e2m3::kRows : panel::kRows;
+    auto grid_for = [&](int rpb) { return (unsigned)(((rows + 8 * kGroupRows - 1) / (8 * kGroupRows)) * 8 * (kGroupRows / rpb)); };
     if (T <= 256) {
         const int rpb = 256 / T;
         hipLaunchKernelGGL((rotquant_kernel<G, U, 256, BITS>), dim3(grid_for(rpb)), dim3(256), 0, stream,

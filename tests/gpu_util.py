@@ -39,23 +39,98 @@ def to_panels(mat: np.ndarray, junk: int = 0x5A) -> np.ndarray:
     return np.ascontiguousarray(a.reshape(rp, 16, kp, 64).transpose(0, 2, 1, 3)).ravel()
 
 
-def unpack_nibbles(packed: np.ndarray) -> np.ndarray:
-    """Row-major packed 4-bit codes [rows, K/2] -> int8 codes [rows, K] (numpy, test side)."""
-    lo = (packed & 0xF).astype(np.int8)
-    hi = (packed >> 4).astype(np.int8)
-    lo = np.where(lo >= 8, lo - 16, lo).astype(np.int8)
-    hi = np.where(hi >= 8, hi - 16, hi).astype(np.int8)
-    out = np.empty((packed.shape[0], packed.shape[1] * 2), dtype=np.int8)
-    out[:, 0::2] = lo
-    out[:, 1::2] = hi
-    return out
+# ---- 4-bit codes as the library stores them: FP6 (E2M3) numbers in 3 KB blocks of 32 rows x 128 codes.
+# Written from the layout's description (include/convrot.h), independently of the library's own code:
+#   unit   16 codes = 96 bits, code e of the unit at bit 6 * (2 * (e % 8) + e // 8)
+#   chunk  an even unit followed by the odd unit after it = 24 bytes: A part = bytes 0-15, B part = bytes 16-23
+#   block  32 rows x 4 chunks: A part of chunk c of row r at r*64 + ((c ^ swz_a(r)) * 16),
+#          B part at 2048 + r*32 + ((c ^ swz_b(r)) * 8); swz_a(r) = ((r>>1) ^ (r>>3)) & 3, swz_b(r) = (r>>3) & 3
+#   matrix block (R, S) of rows 32R.. and codes 128S.. at (R * stages + S) * 3072
+_E2M3_MAG = np.array([0, 0b01000, 0b10000, 0b10100, 0b11000, 0b11010, 0b11100, 0b11110], dtype=np.uint8)   # |q| -> e2m3 bits
+_E2M3_VAL = {int(bits): mag for mag, bits in enumerate(_E2M3_MAG)}
+
+
+def _unit_field_order() -> np.ndarray:
+    """field index (position in the 96-bit string, in units of 6 bits) of code e of a unit"""
+    e = np.arange(16)
+    return 2 * (e % 8) + e // 8
+
+
+def _swz_a(r):
+    return ((r >> 1) ^ (r >> 3)) & 3
+
+
+def _swz_b(r):
+    return (r >> 3) & 3
+
+
+def _chunk_byte_index(rows_pad: int, stages: int):
+    """For every (row, stage, chunk): start offsets of its A part and B part in the matrix buffer."""
+    r = np.arange(rows_pad)[:, None, None]
+    st = np.arange(stages)[None, :, None]
+    c = np.arange(4)[None, None, :]
+    base = ((r // 32) * stages + st) * 3072
+    r32 = r % 32
+    a = base + r32 * 64 + ((c ^ _swz_a(r32)) * 16)
+    b = base + 2048 + r32 * 32 + ((c ^ _swz_b(r32)) * 8)
+    return a, b
+
+
+def encode_e2m3(codes: np.ndarray, junk: int = 0x5A) -> np.ndarray:
+    """int8 codes [rows, K] in [-7, 7] -> the library's 4-bit code matrix (uint8 buffer).  The K padding of the
+    last stage is zero codes, as the library requires; the rows past `rows` of the last block are `junk`."""
+    rows, K = codes.shape
+    stages, rows_pad = -(-K // 128), -(-rows // 32) * 32
+    c = np.zeros((rows, stages * 128), dtype=np.int8)
+    c[:, :K] = codes
+    fp6 = (_E2M3_MAG[np.abs(c)] | np.where(c < 0, 32, 0)).astype(np.uint8)            # [rows, Kpad] 6-bit values
+    units = fp6.reshape(rows, stages * 8, 16)
+    bits = np.zeros((rows, stages * 8, 96), dtype=np.uint8)                              # bit strings, LSB first
+    order = _unit_field_order()
+    for e in range(16):
+        for k in range(6):
+            bits[:, :, 6 * order[e] + k] = (units[:, :, e] >> k) & 1
+    unit_bytes = np.packbits(bits, axis=2, bitorder="little")                           # [rows, units, 12]
+    chunk = unit_bytes.reshape(rows, stages, 4, 24)
+    buf = np.full(rows_pad // 32 * stages * 3072, junk, dtype=np.uint8)
+    a, b = _chunk_byte_index(rows_pad, stages)
+    ai = (a[:rows, :, :, None] + np.arange(16)).ravel()
+    bi = (b[:rows, :, :, None] + np.arange(8)).ravel()
+    buf[ai] = chunk[:, :, :, :16].ravel()
+    buf[bi] = chunk[:, :, :, 16:].ravel()
+    return buf
+
+
+def decode_e2m3(buf: np.ndarray, rows: int, K: int) -> np.ndarray:
+    """The library's 4-bit code matrix -> int8 codes [rows, K].  Checks that every 6-bit field is one of the 15
+    codes (a negative zero is accepted as 0) and that the K padding holds zero codes."""
+    stages, rows_pad = -(-K // 128), -(-rows // 32) * 32
+    buf = np.ascontiguousarray(buf).view(np.uint8).ravel()
+    assert buf.size >= rows_pad // 32 * stages * 3072, "code matrix shorter than its layout"
+    a, b = _chunk_byte_index(rows_pad, stages)
+    ai = a[:rows, :, :, None] + np.arange(16)
+    bi = b[:rows, :, :, None] + np.arange(8)
+    chunk = np.concatenate([buf[ai], buf[bi]], axis=3)                                   # [rows, stages, 4, 24]
+    bits = np.unpackbits(chunk.reshape(rows, stages * 8, 12), axis=2, bitorder="little")  # [rows, units, 96]
+    fields = bits.reshape(rows, stages * 8, 16, 6)
+    val6 = (fields * (1 << np.arange(6, dtype=np.uint8))).sum(axis=3).astype(np.uint8)     # field-ordered
+    fp6 = val6[:, :, _unit_field_order()]                                                # code-ordered
+    mag_bits = fp6 & 31
+    lut = np.full(32, -1, dtype=np.int16)
+    for bits_, mag in _E2M3_VAL.items():
+        lut[bits_] = mag
+    mag = lut[mag_bits]
+    assert (mag >= 0).all(), "a 6-bit field is not the E2M3 code of an integer in [-7, 7]"
+    codes = np.where(fp6 & 32, -mag, mag).astype(np.int8).reshape(rows, stages * 128)
+    assert not codes[:, K:].any(), "K padding of a code matrix must be zero codes"
+    return np.ascontiguousarray(codes[:, :K])
 
 
 def unpack_host(buf, rows: int, K: int) -> np.ndarray:
     """4-bit code matrix as the library stores it (tensor or array) -> int8 codes [rows, K]."""
     if isinstance(buf, torch.Tensor):
         buf = buf.cpu().numpy()
-    return unpack_nibbles(from_panels(buf, rows, K // 2))
+    return decode_e2m3(buf, rows, K)
 
 
 def unpack_host8(buf, rows: int, K: int) -> np.ndarray:
@@ -67,9 +142,7 @@ def unpack_host8(buf, rows: int, K: int) -> np.ndarray:
 
 def codes4_to_dev(codes: np.ndarray) -> torch.Tensor:
     """int8 codes [rows, K] in [-7, 7] -> 4-bit code matrix on the GPU, in the library's layout."""
-    c = codes.astype(np.uint8) & 0xF
-    packed = (c[:, 0::2] | (c[:, 1::2] << 4)).astype(np.uint8)
-    return torch.from_numpy(to_panels(packed)).cuda()
+    return torch.from_numpy(encode_e2m3(codes)).cuda()
 
 
 def codes8_to_dev(codes: np.ndarray) -> torch.Tensor:

@@ -37,16 +37,17 @@ def test_header_symbols_are_exported(lib):
 def test_size_queries_and_strings(lib):
     from paper_2512_03673_amd import binding as b
     assert b.version() == 300
-    # code matrices: 1 KB panels of 16 rows x 64 bytes, rows and K padded up to whole panels
-    assert b.packed_bytes(4608, 3072) == 4608 * 1536
-    assert b.packed_bytes(37, 96) == 3 * 1 * 1024 and b.packed_bytes(3, 32) == 1024
-    assert b.packed_bytes(16, 128) == 1024 and b.packed_bytes(17, 160) == 2 * 2 * 1024
+    # 4-bit code matrices: 3 KB blocks of 32 rows x 128 codes (6 bits per code), rows and K padded up to whole blocks
+    assert b.packed_bytes(4608, 3072) == 4608 * 3072 * 3 // 4
+    assert b.packed_bytes(37, 96) == 2 * 1 * 3072 and b.packed_bytes(3, 32) == 3072
+    assert b.packed_bytes(32, 128) == 3072 and b.packed_bytes(33, 160) == 2 * 2 * 3072
     assert b.packed_bytes(0, 32) == 0
     assert b.packed_bytes(-1, 32) == 0 and b.packed_bytes(4, 33) == 0
+    # 8-bit code matrices: 1 KB panels of 16 rows x 64 bytes
     assert b.packed_bytes8(37, 96) == 3 * 2 * 1024 and b.packed_bytes8(4608, 3072) == 4608 * 3072
     # code matrix + scales rounded up to 256 B
-    assert b.workspace_bytes(4608, 3072) == 4608 * 1536 + 4608 * 4
-    assert b.workspace_bytes(3, 32) == 1024 + 256
+    assert b.workspace_bytes(4608, 3072) == 4608 * 3072 * 3 // 4 + 4608 * 4
+    assert b.workspace_bytes(3, 32) == 3072 + 256
     assert b.workspace_bytes(0, 32) == 0
     assert b.workspace_bytes8(4608, 3072) == 4608 * 3072 + 4608 * 4
     assert b.workspace_bytes8(3, 32) == 1024 + 256

@@ -10,7 +10,7 @@ import torch
 
 import oracle
 from gpu_util import (bf16_to_host_bits, bf16_ulp_diff, bits_to_f64, check_codes, check_output, codes4_to_dev,
-                      to_dev_bf16, unpack_host)
+                      encode_e2m3, to_dev_bf16, unpack_host)
 from paper_2512_03673_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -77,18 +77,18 @@ def test_rotquant_closed_forms_on_gpu(cr, g):
 
 
 def test_rotquant_leaves_padding_rows_alone_and_zeroes_k_padding(cr):
-    # 37 rows of K = 96: 3 row panels (the last with 5 valid rows), one K-panel of 48 code bytes + 16 of padding
+    # 37 rows of K = 96: two 32-row blocks (the second with 5 valid rows) of one K128 stage, whose last chunk is padding
     M, K, g = 37, 96, 16
     rng = np.random.default_rng(5)
     x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
     q = torch.full((cr.packed_bytes(M, K),), 0xAB, dtype=torch.uint8, device="cuda")
-    assert q.numel() == 3 * 1024
+    assert q.numel() == 2 * 3072
     cr.convrot_rotquant_act(to_dev_bf16(x), g, q)
     torch.cuda.synchronize()
-    raw = q.cpu().numpy().reshape(3, 16, 64)
-    assert (raw[2, 5:] == 0xAB).all(), "rows past M were written"
-    assert not raw.reshape(48, 64)[:M, 48:].any(), "K padding is not zero"
-    assert np.array_equal(unpack_host(q, M, K), oracle.rotquant(x, g)[0])
+    raw = q.cpu().numpy()
+    touched = encode_e2m3(np.zeros((M, K), dtype=np.int8), junk=1) != 1      # bytes that belong to rows < M
+    assert (raw[~touched] == 0xAB).all(), "bytes of rows past M were written"
+    assert np.array_equal(unpack_host(q, M, K), oracle.rotquant(x, g)[0])   # also checks the zero K padding
 
 
 def test_prepare_weight_is_the_same_operation(cr):
