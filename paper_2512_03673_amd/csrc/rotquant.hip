@@ -237,16 +237,18 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
         for (int i = 0; i < U; i += 2) {
             const bool pair = i + 1 < U;
             const int i1 = pair ? i + 1 : i;
+            // the two brackets agree on every code exactly when the sum of |difference of their bit patterns|
+            // is zero (the patterns share their upper halves, so the 16-bit SAD sees the whole difference)
             uint32_t disagree = 0;
             v16f qa, qb;    // conversion sources
 #pragma unroll
             for (int e = 0; e < kUnit; ++e) {
                 const float lo0 = fmaf(v[i][e], r_lo, kMagic), hi0 = fmaf(v[i][e], r_hi, kMagic);
-                disagree |= __float_as_uint(lo0) ^ __float_as_uint(hi0);
+                disagree = __builtin_amdgcn_sad_u16(__float_as_uint(lo0), __float_as_uint(hi0), disagree);
                 float q1 = 0.0f;
                 if (pair) {
                     const float lo1 = fmaf(v[i1][e], r_lo, kMagic), hi1 = fmaf(v[i1][e], r_hi, kMagic);
-                    disagree |= __float_as_uint(lo1) ^ __float_as_uint(hi1);
+                    disagree = __builtin_amdgcn_sad_u16(__float_as_uint(lo1), __float_as_uint(hi1), disagree);
                     q1 = lo1 - kMagic;
                 }
                 if (e < 8) { qa[e] = lo0 - kMagic; qa[8 + e] = q1; }
