@@ -56,8 +56,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
 
 // Tile order: blocks are dealt round-robin to the 8 XCDs by the hardware, each XCD has its own
 // L2.  Give every XCD one contiguous range of logical tile ids, and walk that range in bands of
-// `GM` tile rows so that tiles that run together share X and W panels.  `bid` may run past the
+// `GM` tile rows (a template parameter: 6 suits 256 x 128 tiles, 8 square ones) so that tiles that run together share X and W panels.  `bid` may run past the
 // grid (a persistent block asks for bid + gridDim.x, ...): false when XCD bid % 8 has no such tile.
+template <int GM = 6>
 __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n, int &tm, int &tn)
 {
     const int ntiles = tiles_m * tiles_n;
@@ -65,7 +66,6 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
     if (bid / kNumXcd >= per_xcd) return false;
     const int id = (bid % kNumXcd) * per_xcd + bid / kNumXcd;
     if (id >= ntiles) return false;
-    constexpr int GM = 6;
     const int band = id / (GM * tiles_n);
     const int first_m = band * GM;
     const int rows_in_band = min(GM, tiles_m - first_m);

@@ -14,8 +14,10 @@
 // codes and 113-135 us on real ones, and a register-only loop sustains 2.7 POP/s of int8 MFMA against
 // 6.6 POP/s of FP6 MFMA on workload-like data.)
 //
-// Data movement.  A block owns a 256 x 128 output tile (4 wavefronts, 128 x 64 each, 128 accumulator
-// registers per lane) and needs 74 KB of LDS, so that two blocks share a compute unit: while one runs
+// Data movement.  A block owns a 192 x 192 output tile (4 wavefronts, 96 x 96 each: 3 x 3 accumulator
+// tiles, 144 registers per lane, nine MFMAs on six fragments per K64 step; FLUX's layer widths and token
+// counts are multiples of 192, and the headline shape is exactly three rounds of 512 such tiles) and
+// needs 74 KB of LDS, so that two blocks share a compute unit: while one runs
 // its prologue or epilogue, or waits at a barrier, the other keeps the MFMA pipe busy.  The operands
 // sit in HBM as 3 KB blocks of 32 rows x 128 codes (an A plane of 32 x 64 bytes and a B plane of
 // 32 x 32 bytes, both XOR-swizzled for the fragment reads); a K128 stage of the tile is 12 such blocks
@@ -48,9 +50,11 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;                 // 4 wavefronts, 2 x 2
-constexpr int TM = 256, TN = 128;             // block tile
-constexpr int WM = 128, WN = 64;              // wavefront tile
-constexpr int XF = WM / 32, WF = WN / 32;     // fragments (32 rows x one K64 step) per wavefront: 4 of X, 2 of W
+constexpr int TM = 192, TN = 192;             // block tile
+constexpr int WM = 96, WN = 96;               // wavefront tile
+constexpr int XF = WM / 32, WF = WN / 32;     // fragments (32 rows x one K64 step) per wavefront: 3 of X, 3 of W
+constexpr int kMfmas = XF * WF;               // per K64 step: 9
+constexpr int kBandRows = 8;                  // tile rows per band of the XCD-aware tile order (64 square tiles run per XCD)
 constexpr int NF = XF + WF;
 constexpr int kTileBlocks = (TM + TN) / e2m3::kRows;             // 32-row blocks of a stage: 8 of X, then 4 of W
 constexpr int kAPlane = (TM + TN) * e2m3::kARowBytes;            // LDS stage: A parts, tile row r at r * 64 ... 24 KB
@@ -64,7 +68,7 @@ constexpr int kLdsTotal = kRingBytes + (TM + 2 * TN) * 4;        // + the tile's
 static_assert(kLoads * 4 * 1024 == kStageBytes && kTileBlocks * 3 == kLoads * 4, "stage must split into 1 KB loads over 4 wavefronts");
 static_assert(4 * 32 * kEpiPitch <= kRingBytes, "epilogue staging must fit the ring");
 static_assert(2 * kLdsTotal <= 160 * 1024, "two blocks per compute unit");
-static_assert(NF == 6 && kLoads == 9, "slot plan of a K64 step");
+static_assert(NF == 6 && kLoads == 9 && kMfmas == 9, "slot plan of a K64 step");
 
 }  // namespace
 
@@ -78,7 +82,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
     int tm, tn;
-    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    if (!tile_of_block<kBandRows>(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int m0 = tm * TM, n0 = tn * TN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
@@ -89,7 +93,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     // the ring) once the loop is over.
     float my_sx = 0.0f, my_sw = 0.0f, my_b = 0.0f;
     if constexpr (!RAW) {
-        if (m0 + tid < M) my_sx = x_scale[m0 + tid];
+        if (tid < TM && m0 + tid < M) my_sx = x_scale[m0 + tid];
         if (tid < TN && n0 + tid < N) {
             my_sw = w_scale[n0 + tid];
             if (bias) my_b = gemm::bf16_to_f32(bias[n0 + tid]);
@@ -157,12 +161,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     //   slot m: MFMA (i = m % 4, j = m / 4) on the fragments of step KSI;  m < 6: fetch fragment m of the
     //   next step (stage ns, the other K64 parity);  REFILL: LDS-direct loads m (and 8 in slot 0) of stage rs
     auto slot = [&](auto MI, auto KSI, auto REFILL, int ns, int rs) {
-        constexpr int m = decltype(MI)::value, ks = decltype(KSI)::value, i = m % 4, j = m / 4;
+        constexpr int m = decltype(MI)::value, ks = decltype(KSI)::value, i = m % XF, j = m / XF;
         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(op[ks][XF + j], op[ks][i], acc[i][j], 2, 2, 0, 0, 0, 0);
-        if constexpr (decltype(REFILL)::value) {
-            load_stage_part(rs, std::integral_constant<int, m>{});
-            if constexpr (m == 0) load_stage_part(rs, std::integral_constant<int, 8>{});
-        }
+        if constexpr (decltype(REFILL)::value) load_stage_part(rs, std::integral_constant<int, m>{});
         if constexpr (m < NF) read_frag(ns, std::integral_constant<int, 1 - ks>{}, std::integral_constant<int, m>{});
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -170,6 +171,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
         __builtin_amdgcn_sched_barrier(0);
 #define CONVROT_SLOT(m) slot(std::integral_constant<int, m>{}, KSI, REFILL, ns, rs);
         CONVROT_SLOT(0) CONVROT_SLOT(1) CONVROT_SLOT(2) CONVROT_SLOT(3) CONVROT_SLOT(4) CONVROT_SLOT(5) CONVROT_SLOT(6) CONVROT_SLOT(7)
+        CONVROT_SLOT(8)
 #undef CONVROT_SLOT
     };
     // The block meets once per stage, between its two K64 steps: every wavefront has then read all of
@@ -245,7 +247,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
         }
     } else {
         float *sx_lds = reinterpret_cast<float *>(lds + kRingBytes), *sw_lds = sx_lds + TM;
-        sx_lds[tid] = my_sx;
+        if (tid < TM) sx_lds[tid] = my_sx;
         if (tid < TN) {
             sw_lds[tid] = my_sw;
             sw_lds[TN + tid] = my_b;
@@ -254,18 +256,14 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
         // `interior`: the tile lies wholly inside Y and rows of Y are 16-byte multiples, so the stores need
         // no bounds checks (uniform over the block).
         const bool interior = m0 + TM <= M && n0 + TN <= N && (N & 7) == 0;
-        float swn[WF][4][4], sxm[XF];
-#pragma unroll
-        for (int j = 0; j < WF; ++j)
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const float4 v = *reinterpret_cast<const float4 *>(sw_lds + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4);
-                swn[j][rb][0] = v.x; swn[j][rb][1] = v.y; swn[j][rb][2] = v.z; swn[j][rb][3] = v.w;
-            }
+        float sxm[XF];
 #pragma unroll
         for (int i = 0; i < XF; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
-        uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x 64 bf16 staging tile
-        const int ncol = n0 + wn0 + (lane & 7) * 8;              // first of this lane's 8 output columns
+        uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x 96 bf16 staging tile
+        // read-back: 16 lanes per row of 192 bytes, 12 of them active, 4 rows per pass
+        const int rb_row = lane >> 4, rb_piece = lane & 15;
+        const bool rb_active = rb_piece < WN / 8;
+        const int ncol = n0 + wn0 + rb_piece * 8;               // first of this lane's 8 output columns
         auto body = [&](auto INTERIOR, auto BIAS) {
 #pragma unroll
             for (int i = 0; i < XF; ++i) {
@@ -274,21 +272,23 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
                 for (int j = 0; j < WF; ++j)
 #pragma unroll
                     for (int rb = 0; rb < 4; ++rb) {
-                        float y[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            y[e] = (acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
-                            if constexpr (decltype(BIAS)::value) y[e] += sw_lds[TN + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4 + e];
-                        }
                         const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
+                        const float4 sw = *reinterpret_cast<const float4 *>(sw_lds + wn0 + col);
+                        float y[4] = {(acc[i][j][rb * 4 + 0] * sxm[i]) * sw.x, (acc[i][j][rb * 4 + 1] * sxm[i]) * sw.y,
+                                      (acc[i][j][rb * 4 + 2] * sxm[i]) * sw.z, (acc[i][j][rb * 4 + 3] * sxm[i]) * sw.w};
+                        if constexpr (decltype(BIAS)::value) {
+                            const float4 b = *reinterpret_cast<const float4 *>(sw_lds + TN + wn0 + col);
+                            y[0] += b.x; y[1] += b.y; y[2] += b.z; y[3] += b.w;
+                        }
                         *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
                             make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
                     }
-                // the same wavefront reads back row-contiguous: 8 lanes cover one 128-byte row, 8 rows per pass
+                // the same wavefront reads back row-contiguous: 12 lanes cover one 192-byte row, 4 rows per pass
 #pragma unroll
-                for (int it = 0; it < 4; ++it) {
-                    const int r = it * 8 + (lane >> 3);
-                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + (lane & 7) * 16);
+                for (int it = 0; it < 8; ++it) {
+                    const int r = it * 4 + rb_row;
+                    if (!rb_active) continue;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + rb_piece * 16);
                     const int mo = mrow + r;
                     uint16_t *dst = Y + (int64_t)mo * N + ncol;
                     if constexpr (decltype(INTERIOR)::value) {
