@@ -30,22 +30,30 @@
  *     bf16 and int32 matrices must be 16-byte aligned, code matrices 256-byte aligned, scale
  *     pointers 4-byte aligned.
  *
- * Codes.  A 4-bit code is a two's complement integer in [-7, 7] (-8 is never produced); a row of K
- * codes is K/2 bytes, byte j holding code 2j in bits 0-3 and code 2j+1 in bits 4-7.  (8-bit variant:
- * one int8 in [-127, 127] per byte, K bytes per row.)
+ * Codes.  A 4-bit code is an integer in [-7, 7] (-8 is never produced).  In memory it is the FP6
+ * (E2M3: 1 sign, 2 exponent, 3 mantissa bits, bias 1) number of that value, six bits, the operand
+ * format of the CDNA4 matrix instruction the GEMM runs on (every such integer is an E2M3 number;
+ * products and their sums up to K = 65536 stay below 2^24, so the fp32 accumulation is exact and
+ * the GEMM is the integer GEMM, bit for bit).  A code matrix of `rows` x K codes is laid out as
  *
- * Panel layout of a code matrix (shared by activations and weights, 4-bit and 8-bit).  The matrix
- * of `rows` rows of B bytes (B = K/2, or K for 8-bit codes) is stored as 1 KB panels of 16 rows x
- * 64 bytes, the K-panels of the same 16 rows adjacent:
+ *   unit    16 consecutive codes of a row = 96 bits (3 little-endian dwords); code e of the unit
+ *           sits at bit 6 * (2 * (e % 8) + e / 8)
+ *   chunk   an even unit followed by the odd unit after it = 32 codes = 24 bytes:
+ *           "A part" = its first 16 bytes, "B part" = its last 8
+ *   block   32 rows x 128 codes (4 chunks per row) = 3 KB:
+ *             A part of chunk c of row r  at  r * 64 + ((c ^ (((r >> 1) ^ (r >> 3)) & 3)) * 16)
+ *             B part                      at  2048 + r * 32 + ((c ^ ((r >> 3) & 3)) * 8)
+ *   matrix  block (R, S) - rows 32 R .., codes 128 S .. - at (R * ceil(K / 128) + S) * 3072
  *
- *     byte b of row r  at  ((r / 16) * KP + b / 64) * 1024 + (r % 16) * 64 + b % 64,   KP = ceil(B / 64)
- *
- * so that the GEMM's loads (16 rows x 64 bytes of K at a time) are contiguous kilobytes.  A code
- * matrix therefore occupies ceil(rows / 16) * KP * 1024 bytes (convrot_packed_bytes): bytes of the
- * last K-panel past B are written as zero codes by the producing call, the rows past `rows` of the
- * last row panel are never read or written (a caller that fills a code matrix itself must zero
- * that K padding too).  The layout is a contract between the producing calls
- * (convrot_prepare_weight, convrot_rotquant_act) and the GEMM calls of the same library version.
+ * i.e. ceil(rows / 32) * ceil(K / 128) * 3072 bytes (convrot_packed_bytes).  The codes of the last
+ * block of a row past K are written as zeros by the producing call, the rows past `rows` of the
+ * last row block are never read or written (a caller that fills a code matrix itself must zero
+ * that K padding too).  (8-bit variant: one int8 in [-127, 127] per code, K bytes per row, stored
+ * as 1 KB panels of 16 rows x 64 bytes, the K-panels of the same 16 rows adjacent: byte b of row r
+ * at ((r / 16) * KP + b / 64) * 1024 + (r % 16) * 64 + b % 64, KP = ceil(K / 64), same padding
+ * rules; convrot_packed_bytes8.)  Both layouts exist so that the GEMM's loads are whole contiguous
+ * kilobytes; they are a contract between the producing calls (convrot_prepare_weight,
+ * convrot_rotquant_act) and the GEMM calls of the same library version.
  *
  * Quantiser (both operands): a = max_k |x'[k]| over the rotated row, s = a / 7 in fp32 (s = 1
  * when a == 0), q = clamp(round_half_even(x' / s), -7, 7).
@@ -60,7 +68,7 @@
 extern "C" {
 #endif
 
-#define CONVROT_VERSION 300          /* major*10000 + minor*100 + patch */
+#define CONVROT_VERSION 400          /* major*10000 + minor*100 + patch */
 #define CONVROT_MAX_K 65536          /* longest row the single-pass rotate+quantise kernel holds on chip */
 
 typedef enum convrot_status {
@@ -79,8 +87,8 @@ const char *convrot_status_string(int status);
 /* Host.  CONVROT_VERSION of the loaded library. */
 int convrot_version(void);
 
-/* Host.  Bytes of a 4-bit code matrix with `rows` rows of K codes in the panel layout
- * (ceil(rows / 16) * ceil(K / 128) KB).  0 on bad input. */
+/* Host.  Bytes of a 4-bit code matrix with `rows` rows of K codes in the layout above
+ * (ceil(rows / 32) * ceil(K / 128) * 3 KB: 0.75 byte per code).  0 on bad input. */
 size_t convrot_packed_bytes(int64_t rows, int64_t K);
 
 /* Host.  Bytes of workspace convlinear4bit_forward needs for an [M, K] activation: the code matrix
@@ -91,7 +99,7 @@ size_t convrot_workspace_bytes(int64_t M, int64_t K);
  * Offline weight preparation (Eq. 12-13, Sec. 5.2 "per-channel"): W' = R_g(W); for each output
  * channel n, s_w[n] = max_k |W'[n,k]| / 7 and q_w[n,:] = Q4(W'[n,:]); packed.
  *   W_bf16   DEVICE in   [N, K] bf16
- *   Wq       DEVICE out  convrot_packed_bytes(N, K) bytes: 4-bit codes [N, K], panel layout
+ *   Wq       DEVICE out  convrot_packed_bytes(N, K) bytes: 4-bit codes [N, K], layout above
  *   w_scale  DEVICE out  [N] fp32
  */
 int convrot_prepare_weight(const void *W_bf16, int64_t N, int64_t K, int group,
@@ -101,7 +109,7 @@ int convrot_prepare_weight(const void *W_bf16, int64_t N, int64_t K, int group,
  * Online activation path (Sec. 4.2 + Eq. 1, Sec. 5.2 "per-token"): X' = R_g(X), per-token scale,
  * 4-bit codes, packed - one pass over X.
  *   X_bf16   DEVICE in   [M, K] bf16
- *   Xq       DEVICE out  convrot_packed_bytes(M, K) bytes: 4-bit codes [M, K], panel layout
+ *   Xq       DEVICE out  convrot_packed_bytes(M, K) bytes: 4-bit codes [M, K], layout above
  *   x_scale  DEVICE out  [M] fp32
  */
 int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group,
@@ -109,8 +117,8 @@ int convrot_rotquant_act(const void *X_bf16, int64_t M, int64_t K, int group,
 
 /*
  * W4A4 GEMM with the dequantisation fused (Sec. 4.3; suppl. Sec. B lists them as two stages):
- * Y[m,n] = bf16( (sum_k q_x[m,k] q_w[n,k]) * x_scale[m] * w_scale[n] + bias[n] ).
- *   Xq, Wq            DEVICE in   4-bit codes [M, K], [N, K], panel layout
+ * Y[m,n] = bf16( (sum_k q_x[m,k] q_w[n,k]) * x_scale[m] * w_scale[n] + bias[n] ), the sum exact.
+ *   Xq, Wq            DEVICE in   4-bit codes [M, K], [N, K], layout above
  *   x_scale, w_scale  DEVICE in   [M], [N] fp32
  *   bias_bf16         DEVICE in   [N] bf16, or NULL for none.  Eq. 10 of the paper has no bias; the
  *                                 linear layers it replaces carry one, added here in fp32 before the
@@ -143,6 +151,15 @@ int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
  */
 int convrot_w4a4_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K,
                           int32_t *acc, void *stream);
+
+/*
+ * Gate / debug export, not a hot-path call: the codes of a 4-bit code matrix as plain integers, so that
+ * what convrot_prepare_weight and convrot_rotquant_act produced can be compared code by code
+ * (Eq. 1) without knowing the layout.
+ *   Xq     DEVICE in   4-bit codes [rows, K], layout above
+ *   codes  DEVICE out  [rows, K] int8, row-major, each in [-7, 7]; 16-byte aligned
+ */
+int convrot_unpack_codes(const void *Xq, int64_t rows, int64_t K, int8_t *codes, void *stream);
 
 /*
  * Diagnostic, not a hot-path call: the paper's outlier-amplitude metric max |X H| (Sec. 4.2; Table 5-1

@@ -24,7 +24,7 @@ EXPORTS = ("convrot_status_string", "convrot_version", "convrot_packed_bytes", "
            "convlinear4bit_forward", "convrot_w4a4_gemm_i32",
            "convrot_prepare_weight8", "convrot_rotquant_act8", "convrot_w8a8_gemm_dequant",
            "convlinear8bit_forward", "convrot_w8a8_gemm_i32", "convrot_rotated_absmax",
-           "convrot_workspace_bytes8", "convrot_packed_bytes8")
+           "convrot_workspace_bytes8", "convrot_packed_bytes8", "convrot_unpack_codes")
 
 _lib = None
 
@@ -69,7 +69,9 @@ def load() -> ctypes.CDLL:
     lib.convrot_rotated_absmax.argtypes = [vp, i64, i64, i32, i32, vp, vp]
     lib.convrot_packed_bytes8.argtypes = [i64, i64]
     lib.convrot_packed_bytes8.restype = sz
-    for name in EXPORTS[4:-2]:
+    lib.convrot_unpack_codes.argtypes = [vp, i64, i64, vp, vp]
+    lib.convrot_unpack_codes.restype = i32
+    for name in EXPORTS[4:-3]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -160,6 +162,15 @@ def convrot_rotquant_act(X: torch.Tensor, group: int, Xq: Optional[torch.Tensor]
     _check(load().convrot_rotquant_act(_ptr(X), M, K, group, _ptr(Xq), _ptr(x_scale), _stream(stream)),
            "convrot_rotquant_act")
     return Xq, x_scale
+
+
+def convrot_unpack_codes(Xq: torch.Tensor, rows: int, K: int, codes: Optional[torch.Tensor] = None,
+                         stream=None) -> torch.Tensor:
+    """4-bit code matrix -> int8 codes [rows, K] (gate / debug export)."""
+    _codes(Xq, packed_bytes(rows, K), "Xq")
+    codes = torch.empty((rows, K), dtype=torch.int8, device=Xq.device) if codes is None else codes
+    _check(load().convrot_unpack_codes(_ptr(Xq), rows, K, _ptr(codes), _stream(stream)), "convrot_unpack_codes")
+    return codes
 
 
 def convrot_w4a4_gemm_dequant(Xq: torch.Tensor, x_scale: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor,

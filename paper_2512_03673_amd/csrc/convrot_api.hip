@@ -111,6 +111,15 @@ int convrot_w4a4_gemm_i32(const void *Xq, const void *Wq, int64_t M, int64_t N, 
     return from_hip(convrot::launch_gemm_w4a4(Xq, nullptr, Wq, nullptr, nullptr, M, N, K, nullptr, acc, (hipStream_t)stream));
 }
 
+int convrot_unpack_codes(const void *Xq, int64_t rows, int64_t K, int8_t *codes, void *stream)
+{
+    if (rows < 0 || rows > INT32_MAX) return CONVROT_ERR_SHAPE;
+    if (int rc = check_k(K)) return rc;
+    if (missing(Xq, rows) || missing(codes, rows)) return CONVROT_ERR_NULL;
+    if (!aligned(Xq, 256) || !aligned(codes, 16)) return CONVROT_ERR_ALIGN;
+    return from_hip(convrot::launch_unpack_codes(Xq, rows, K, codes, (hipStream_t)stream));
+}
+
 int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16,
                            int64_t M, int64_t N, int64_t K, int group, void *Y_bf16, void *workspace,
                            size_t workspace_bytes, void *stream)

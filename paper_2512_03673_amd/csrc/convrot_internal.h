@@ -11,6 +11,9 @@ namespace convrot {
 hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, int bits, void *Xq, float *scale,
                            hipStream_t stream);
 
+// 4-bit code matrix (FP6 layout) -> int8 codes [rows, K], row-major.
+hipError_t launch_unpack_codes(const void *Xq, int64_t rows, int64_t K, int8_t *codes, hipStream_t stream);
+
 // Per-row max |R(X)| for kind 0 = no rotation, 1 = the regular Hadamard rotation, 2 = Sylvester (diagnostic).
 hipError_t launch_rotated_absmax(const void *X, int64_t rows, int64_t K, int group, int kind, float *out,
                                  hipStream_t stream);

@@ -472,6 +472,46 @@ hipError_t launch_absmax_g(const void *X, int64_t rows, int K, int kind, float *
 
 }  // namespace
 
+// ---- code matrix -> plain int8 codes (gate / debug export)
+__global__ __launch_bounds__(256) void unpack_codes_kernel(const uint8_t *__restrict__ Xq, int64_t rows, int K,
+                                                           int8_t *__restrict__ codes)
+{
+    // one thread per unit of 16 codes: its 12 bytes are the first or the last 12 of a 24-byte chunk
+    const int units = K / kUnit;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= rows * units) return;
+    const int64_t row = id / units;
+    const int unit = (int)(id - row * units);
+    const uint8_t *blk = Xq + ((row / e2m3::kRows) * e2m3::stages(K) + unit / e2m3::kUnitsPerStage) * e2m3::kBlockBytes;
+    const int r = (int)(row % e2m3::kRows), c = (unit % e2m3::kUnitsPerStage) >> 1;
+    const uint32_t *pa = reinterpret_cast<const uint32_t *>(blk + e2m3::a_offset(r, c));
+    const uint32_t *pb = reinterpret_cast<const uint32_t *>(blk + e2m3::b_offset(r, c));
+    uint32_t w[3];
+    if ((unit & 1) == 0) { w[0] = pa[0]; w[1] = pa[1]; w[2] = pa[2]; }
+    else { w[0] = pa[3]; w[1] = pb[0]; w[2] = pb[1]; }
+    int8_t out[kUnit];
+#pragma unroll
+    for (int e = 0; e < kUnit; ++e) {
+        const int bit = 6 * (2 * (e % 8) + e / 8);
+        uint32_t f = w[bit / 32] >> (bit % 32);
+        if (bit % 32 > 26) f |= w[bit / 32 + 1] << (32 - bit % 32);
+        const int ex = (f >> 3) & 3, mant = f & 7;
+        const int mag = ex == 0 ? 0 : ((8 | mant) << ex) >> 4;   // E2M3, bias 1: (1 + mant / 8) * 2^(ex - 1)
+        out[e] = (int8_t)((f & 32) ? -mag : mag);
+    }
+    int4 *dst = reinterpret_cast<int4 *>(codes + row * (int64_t)K + (int64_t)unit * kUnit);
+    *dst = *reinterpret_cast<const int4 *>(out);
+}
+
+hipError_t launch_unpack_codes(const void *Xq, int64_t rows, int64_t K, int8_t *codes, hipStream_t stream)
+{
+    if (rows == 0) return hipSuccess;
+    const int64_t n = rows * (K / kUnit);
+    hipLaunchKernelGGL(unpack_codes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (const uint8_t *)Xq, rows,
+                       (int)K, codes);
+    return hipGetLastError();
+}
+
 hipError_t launch_rotated_absmax(const void *X, int64_t rows, int64_t K, int group, int kind, float *out,
                                  hipStream_t stream)
 {

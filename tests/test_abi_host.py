@@ -28,7 +28,7 @@ def declared_symbols():
 def test_header_symbols_are_exported(lib):
     from paper_2512_03673_amd import binding
     names = declared_symbols()
-    assert len(names) == 17
+    assert len(names) == 18
     assert sorted(binding.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -36,7 +36,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_size_queries_and_strings(lib):
     from paper_2512_03673_amd import binding as b
-    assert b.version() == 300
+    assert b.version() == 400
     # 4-bit code matrices: 3 KB blocks of 32 rows x 128 codes (6 bits per code), rows and K padded up to whole blocks
     assert b.packed_bytes(4608, 3072) == 4608 * 3072 * 3 // 4
     assert b.packed_bytes(37, 96) == 2 * 1 * 3072 and b.packed_bytes(3, 32) == 3072
@@ -102,6 +102,8 @@ def test_argument_validation_without_a_device(lib):
     assert fw8(A, A, A, None, 4, 4, 1024, 16, A, A, 100, None) == -5
     assert fw8(A, A, A, None, 4, 4, 1040, 16, A, A, 1 << 20, None) == -2
     assert g8(A, A, A, A, None, 0, 4, 1024, A, None) == 0
+    u = lib.convrot_unpack_codes
+    assert u(None, 4, 1024, A, None) == -1 and u(A, 4, 1000, A, None) == -2 and u(A, 4, 1024, A + 8, None) == -4
     d = lib.convrot_rotated_absmax
     assert d(A, 4, 1024, 16, 3, A, None) == -3 and d(A, 4, 1024, 8, 1, A, None) == -3
     assert d(None, 4, 1024, 16, 1, A, None) == -1 and d(A, 4, 1000, 16, 1, A, None) == -2

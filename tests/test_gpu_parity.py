@@ -91,6 +91,21 @@ def test_rotquant_leaves_padding_rows_alone_and_zeroes_k_padding(cr):
     assert np.array_equal(unpack_host(q, M, K), oracle.rotquant(x, g)[0])   # also checks the zero K padding
 
 
+def test_unpack_codes_agrees_with_the_layout_description(cr):
+    # the library's own decoder against the numpy decoder written from the header's description, on codes that
+    # exercise every value, ragged rows and a padded last block
+    rng = np.random.default_rng(9)
+    for rows, K in ((37, 96), (64, 128), (130, 3072), (3, 65536)):
+        codes = rng.integers(-7, 8, size=(rows, K)).astype(np.int8)
+        dev = codes4_to_dev(codes)
+        out = cr.convrot_unpack_codes(dev, rows, K)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), codes)
+    x = wl.make_activation(wl.CONFIGS["cfg1_tiny"][0])
+    q, _ = cr.convrot_rotquant_act(to_dev_bf16(x), 16)
+    assert np.array_equal(cr.convrot_unpack_codes(q, *x.shape).cpu().numpy(), unpack_host(q, *x.shape))
+
+
 def test_prepare_weight_is_the_same_operation(cr):
     spec = wl.CONFIGS["cfg1_tiny"][0]
     w = wl.make_weight(spec)
