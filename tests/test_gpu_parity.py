@@ -129,6 +129,26 @@ def test_gemm_i32_bit_exact(cr, M, N, K):
     assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
 
 
+def test_gemm_i32_small_products_after_a_large_partial_sum(cr):
+    # The GEMM accumulates in fp32, exactly as long as no partial sum needs more than 24 bits.  The hardest
+    # case for that: a partial sum near the bound (49 * 60000 = 2.94e6), then thousands of products of +-1,
+    # +-2, +-3 added to it, in both signs; any lost low bit shows in the int32 result.
+    M, N, K = 70, 40, 65536
+    rng = np.random.default_rng(17)
+    qx = np.zeros((M, K), dtype=np.int8)
+    qw = np.zeros((N, K), dtype=np.int8)
+    big = 60032                                    # a whole number of K128 stages
+    qx[:, :big] = 7
+    qw[:, :big] = np.where(np.arange(N)[:, None] % 2 == 0, 7, -7)
+    qx[:, big:] = rng.integers(-1, 2, size=(M, K - big))
+    qw[:, big:] = rng.integers(-3, 4, size=(N, K - big))
+    acc = cr.convrot_w4a4_gemm_i32(codes4_to_dev(qx), codes4_to_dev(qw), M, N, K)
+    torch.cuda.synchronize()
+    ref = oracle.int_gemm(qx, qw)
+    assert np.abs(ref).max() > 2_900_000 and (np.abs(ref - np.sign(ref) * 49 * big) > 0).any()
+    assert np.array_equal(acc.cpu().numpy(), ref)
+
+
 @pytest.mark.parametrize("M,N,K", [(300, 520, 1024), (129, 1026, 3072), (31, 5, 64)])
 def test_gemm_dequant_on_identical_codes(cr, M, N, K):
     rng = np.random.default_rng(M + N + K)
