@@ -6,8 +6,8 @@
 
 namespace convrot {
 
-// Rotate + quantise + pack `rows` rows of K bf16 values (group in {4,16,64,256,1024}; bits 4: two codes
-// per byte, bits 8: one int8 per code).  Xq is written in the panel layout (panel_layout.h).
+// Rotate + quantise + pack `rows` rows of K bf16 values (group in {4,16,64,256,1024}; bits 4: FP6 E2M3
+// codes in the layout of e2m3_layout.h, bits 8: one int8 per code in the layout of panel_layout.h).
 hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, int bits, void *Xq, float *scale,
                            hipStream_t stream);
 
@@ -18,7 +18,7 @@ hipError_t launch_unpack_codes(const void *Xq, int64_t rows, int64_t K, int8_t *
 hipError_t launch_rotated_absmax(const void *X, int64_t rows, int64_t K, int group, int kind, float *out,
                                  hipStream_t stream);
 
-// W4A4 GEMM on packed codes in the panel layout.  Exactly one of Y_bf16 / acc_i32 is non-null:
+// W4A4 GEMM on 4-bit code matrices (e2m3_layout.h).  Exactly one of Y_bf16 / acc_i32 is non-null:
 //   Y_bf16 : dequantised bf16 output (needs x_scale, w_scale; bias_bf16 [N] or null)
 //   acc_i32: raw int32 accumulators
 hipError_t launch_gemm_w4a4(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale,

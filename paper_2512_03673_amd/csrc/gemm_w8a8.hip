@@ -293,12 +293,16 @@ hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, cons
     const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
     const int ntiles = tiles_m * tiles_n;
     const int grid = ((ntiles + kNumXcd - 1) / kNumXcd) * kNumXcd;
-    static bool attr_done = false;  // raising the dynamic-LDS limit is idempotent; a race only repeats it
-    if (!attr_done) {
+    // The dynamic-LDS limit of a kernel is a per-device setting: raise it once on every device the
+    // library launches on (idempotent; a race only repeats it).
+    static bool attr_done[64] = {};
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64 || !attr_done[dev]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w8a8_kernel<RAW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        if (dev >= 0 && dev < 64) attr_done[dev] = true;
     }
     hipLaunchKernelGGL((gemm_w8a8_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsTotal, stream, (const uint8_t *)Xq,
                        x_scale, (const uint8_t *)Wq, w_scale, (const uint16_t *)bias, M, N, K, (uint16_t *)Y, acc, tiles_m,

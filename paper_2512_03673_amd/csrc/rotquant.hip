@@ -1,8 +1,8 @@
 // Kernel A of libconvrot: group-wise regular-Hadamard rotation + per-row absmax + 4-bit
-// quantisation + nibble packing, one pass over the bf16 input (ConvRot paper Sec. 4.2 Eq. 11-13,
+// quantisation + packing of the codes, one pass over the bf16 input (ConvRot paper Sec. 4.2 Eq. 11-13,
 // Eq. 1, Sec. 5.2).  Serves activations (rows = tokens) and weights (rows = output channels).
 //
-// Work split.  A "unit" is 16 consecutive elements of a row (32 B of bf16 in, 8 B of codes out)
+// Work split.  A "unit" is 16 consecutive elements of a row (32 B of bf16 in, 12 B of codes out)
 // and belongs to one lane.  A row is spread over T = 64*Wv lanes (Wv wavefronts); lane t of the
 // row owns units t, t+T, t+2T, ... (U of them), so one wavefront load instruction covers a
 // contiguous 2 KB span of the row.  The whole row stays in registers between the absmax
@@ -22,8 +22,8 @@
 // fallback for the few wavefronts that hold a (near-)tie (see the comment at the code).
 // |z| / (2^k s) <= 7 (1 + 2^-22), so no clamp is needed.
 //
-// Output.  The codes leave in the panel layout the GEMM loads from (panel_layout.h): a lane's unit is
-// 8 (or 16) bytes of a 64-byte panel row, so 8 (or 4) neighbouring lanes fill one panel row.
+// Output.  The codes leave in the layouts the GEMMs load from (e2m3_layout.h for 4-bit codes,
+// panel_layout.h for 8-bit ones).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -107,7 +107,8 @@ constexpr float group_norm() { return G == 4 ? 0.5f : G == 16 ? 0.25f : G == 64 
 }  // namespace
 
 // grid.x = 8 * ceil(rows / 128) * 16 / rows_per_block; block = rows_per_block * T threads, T = 64 * waves_per_row.
-// BITS = 4: two codes per byte, [-7, 7]; BITS = 8 (the W8A8 variant of the layer): one int8 per code, [-127, 127].
+// BITS = 4: codes in [-7, 7], stored as FP6 E2M3 (e2m3_layout.h); BITS = 8 (the W8A8 variant of the layer): one
+// int8 per code, [-127, 127] (panel_layout.h).
 template <int G, int U, int BLOCK, int BITS>
 __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
                                                          int T, uint8_t *__restrict__ Xq,
