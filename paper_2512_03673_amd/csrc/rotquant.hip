@@ -106,20 +106,27 @@ constexpr float group_norm() { return G == 4 ? 0.5f : G == 16 ? 0.25f : G == 64 
 
 }  // namespace
 
-// grid.x = 8 * ceil(rows / 128) * 16 / rows_per_block; block = rows_per_block * T threads, T = 64 * waves_per_row.
+// T = lanes per row.  Two ways of laying rows over wavefronts:
+//   RPW = 1  a wavefront holds 64 lanes of one row (T = 64 * waves per row, BLOCK / T rows per block): any K, any g
+//   RPW = 4  a wavefront holds 16 lanes of each of 4 consecutive rows (T = BLOCK / 4, 4 rows per block): g <= 256
+//            (the cross-lane digits stay inside 16 lanes), used for K <= 4096.  The four rows' pieces of an output block
+//            are adjacent in memory, so a store instruction touches 256- and 128-byte runs instead of 64- and
+//            32-byte ones: as few cache lines per instruction as a row-major stream would.
+// grid.x = 8 * ceil(rows / (8 * group rows)) * group rows / rows per block (see the row mapping below).
 // BITS = 4: codes in [-7, 7], stored as FP6 E2M3 (e2m3_layout.h); BITS = 8 (the W8A8 variant of the layer): one
 // int8 per code, [-127, 127] (panel_layout.h).
-template <int G, int U, int BLOCK, int BITS>
+template <int G, int U, int BLOCK, int BITS, int RPW>
 __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
                                                          int T, uint8_t *__restrict__ Xq,
                                                          float *__restrict__ scale)
 {
-    __shared__ float s_part[BLOCK / 64];
+    static_assert(RPW == 1 || (RPW == 4 && G <= 256), "four rows per wavefront need the rotation inside 16 lanes");
+    __shared__ float s_part[BLOCK / 64 * RPW];
 
     const int tid = threadIdx.x;
-    const int rib = tid / T;               // row inside the block
-    const int t = tid - rib * T;           // lane index inside the row
-    const int rows_per_block = BLOCK / T;
+    const int rib = RPW == 1 ? tid / T : (tid & 63) >> 4;                        // row inside the block
+    const int t = RPW == 1 ? tid - rib * T : (tid >> 6) * 16 + (tid & 15);       // lane index inside the row
+    const int rows_per_block = RPW == 1 ? BLOCK / T : RPW;
     // Blocks are dealt round-robin to the 8 XCDs, each with an L2 of its own.  The 16 rows of an output
     // panel go to consecutive blocks of one XCD, so that the 64-byte row pieces of a panel meet in one
     // L2 and leave it as whole lines.
@@ -162,16 +169,27 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
         amax = (row_ok && i * T + t < units) ? fmaxf(amax, m) : amax;
     }
 
-    // row absmax: wavefront butterfly, then across the row's wavefronts through LDS
+    // row absmax: butterfly over the row's lanes of this wavefront, then across the row's wavefronts through LDS
+    if constexpr (RPW == 1) {
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
-    if (T > 64) {
-        if ((tid & 63) == 0) s_part[tid >> 6] = amax;
+        for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
+        if (T > 64) {
+            if ((tid & 63) == 0) s_part[tid >> 6] = amax;
+            __syncthreads();
+            const int w0 = (rib * T) >> 6;
+            const int wv = T >> 6;
+            float a = s_part[w0];
+            for (int w = 1; w < wv; ++w) a = fmaxf(a, s_part[w0 + w]);
+            amax = a;
+        }
+    } else {
+#pragma unroll
+        for (int m = 8; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
+        if ((tid & 15) == 0) s_part[(tid >> 6) * RPW + rib] = amax;
         __syncthreads();
-        const int w0 = (rib * T) >> 6;
-        const int wv = T >> 6;
-        float a = s_part[w0];
-        for (int w = 1; w < wv; ++w) a = fmaxf(a, s_part[w0 + w]);
+        float a = s_part[rib];
+#pragma unroll
+        for (int w = 1; w < BLOCK / 64; ++w) a = fmaxf(a, s_part[w * RPW + rib]);
         amax = a;
     }
 
@@ -400,26 +418,50 @@ hipError_t launch_gu(const void *X, int64_t rows, int K, int waves_per_row, void
                      hipStream_t stream)
 {
     const int T = 64 * waves_per_row;
-    // grid: 8 XCDs x whole row panels per XCD x blocks per panel (see the row mapping in the kernel)
+    // grid: 8 XCDs x whole row groups per XCD x blocks per group (see the row mapping in the kernel)
     constexpr int kGroupRows = BITS == 4 ? e2m3::kRows : panel::kRows;
     auto grid_for = [&](int rpb) { return (unsigned)(((rows + 8 * kGroupRows - 1) / (8 * kGroupRows)) * 8 * (kGroupRows / rpb)); };
     if (T <= 256) {
         const int rpb = 256 / T;
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 256, BITS>), dim3(grid_for(rpb)), dim3(256), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 256, BITS, 1>), dim3(grid_for(rpb)), dim3(256), 0, stream,
                            (const uint16_t *)X, rows, K, T, (uint8_t *)Xq, scale);
     } else if (T <= 512) {
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 512, BITS>), dim3(grid_for(1)), dim3(512), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 512, BITS, 1>), dim3(grid_for(1)), dim3(512), 0, stream,
                            (const uint16_t *)X, rows, K, 512, (uint8_t *)Xq, scale);
     } else {
-        hipLaunchKernelGGL((rotquant_kernel<G, U, 1024, BITS>), dim3(grid_for(1)), dim3(1024), 0, stream,
+        hipLaunchKernelGGL((rotquant_kernel<G, U, 1024, BITS, 1>), dim3(grid_for(1)), dim3(1024), 0, stream,
                            (const uint16_t *)X, rows, K, 1024, (uint8_t *)Xq, scale);
     }
+    return hipGetLastError();
+}
+
+// four rows per wavefront: 4 wavefronts of 16 lanes per row (blocks of 256 threads; with larger blocks, i.e.
+// longer rows, the mapping loses more to the block-wide barrier than the stores gain: measured)
+template <int G, int U, int BITS>
+hipError_t launch_gu4(const void *X, int64_t rows, int K, void *Xq, float *scale, hipStream_t stream)
+{
+    constexpr int kGroupRows = BITS == 4 ? e2m3::kRows : panel::kRows;
+    const unsigned grid = (unsigned)(((rows + 8 * kGroupRows - 1) / (8 * kGroupRows)) * 8 * (kGroupRows / 4));
+    hipLaunchKernelGGL((rotquant_kernel<G, U, 256, BITS, 4>), dim3(grid), dim3(256), 0, stream, (const uint16_t *)X, rows, K,
+                       64, (uint8_t *)Xq, scale);
     return hipGetLastError();
 }
 
 template <int G, int BITS>
 hipError_t launch_g(const void *X, int64_t rows, int K, void *Xq, float *scale, hipStream_t stream)
 {
+    if constexpr (G <= 256) {
+        // four rows per wavefront whenever 4 wavefronts x 16 lanes x 4 units hold a row (K <= 4096)
+        const int spans = (K / kUnit + 15) / 16;   // 256-element spans per row
+        if (spans <= 16) {
+            switch ((spans + 3) / 4) {
+                case 1: return launch_gu4<G, 1, BITS>(X, rows, K, Xq, scale, stream);
+                case 2: return launch_gu4<G, 2, BITS>(X, rows, K, Xq, scale, stream);
+                case 3: return launch_gu4<G, 3, BITS>(X, rows, K, Xq, scale, stream);
+                default: return launch_gu4<G, 4, BITS>(X, rows, K, Xq, scale, stream);
+            }
+        }
+    }
     // Pick the wavefronts per row (1, 2, 4, 8 or 16) so that every lane holds at most 4 units,
     // preferring 3-4 units per lane (enough bytes in flight per wavefront, registers under 128).
     const int chunks = (K / kUnit + 63) / 64;  // 1024-element spans per row
