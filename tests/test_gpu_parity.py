@@ -116,7 +116,8 @@ def test_prepare_weight_is_the_same_operation(cr):
 
 # ------------------------------------------------------------------ kernel B: integer GEMM
 @pytest.mark.parametrize("M,N,K", [(256, 256, 128), (300, 520, 1024), (1, 1, 32), (33, 7, 96), (257, 513, 3072),
-                                   (64, 1030, 12288), (513, 258, 160), (40, 136, 65536), (3, 2, 65504)])
+                                   (64, 1030, 12288), (513, 258, 160), (40, 136, 65536), (3, 2, 65504),
+                                   (192, 192, 128), (193, 385, 160), (191, 383, 96), (577, 190, 416)])
 def test_gemm_i32_bit_exact(cr, M, N, K):
     rng = np.random.default_rng(M * 7 + N * 3 + K)
     qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
@@ -168,7 +169,7 @@ def test_gemm_dequant_on_identical_codes(cr, M, N, K):
     check_output(yb, yo, "dequant")
 
 
-@pytest.mark.parametrize("M,N,K", [(300, 520, 1024), (129, 1026, 3072), (31, 5, 64), (260, 136, 96)])
+@pytest.mark.parametrize("M,N,K", [(300, 520, 1024), (129, 1026, 3072), (31, 5, 64), (260, 136, 96), (193, 391, 224)])
 def test_gemm_dequant_with_bias(cr, M, N, K):
     rng = np.random.default_rng(M * N + K)
     qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
