@@ -44,7 +44,7 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0()
 __device__ __forceinline__ void lds_dma16(const uint8_t *base, uint32_t lane_off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory");
+                 :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
