@@ -68,7 +68,7 @@
 extern "C" {
 #endif
 
-#define CONVROT_VERSION 400          /* major*10000 + minor*100 + patch */
+#define CONVROT_VERSION 401          /* major*10000 + minor*100 + patch */
 #define CONVROT_MAX_K 65536          /* longest row the single-pass rotate+quantise kernel holds on chip */
 
 typedef enum convrot_status {
@@ -86,6 +86,11 @@ const char *convrot_status_string(int status);
 
 /* Host.  CONVROT_VERSION of the loaded library. */
 int convrot_version(void);
+
+/* Host.  X rows per block tile that both GEMM kernels use for an [M, N] output: 192 (tile 192 x 192) or
+ * 256 (tile 256 x 128); 0 when M or N < 0.  The result of the GEMM does not depend on it; the query
+ * exists so that tests and tuning runs can tell which kernel configuration a shape exercises. */
+int convrot_gemm_tile_rows(int64_t M, int64_t N);
 
 /* Host.  Bytes of a 4-bit code matrix with `rows` rows of K codes in the layout above
  * (ceil(rows / 32) * ceil(K / 128) * 3 KB: 0.75 byte per code).  0 on bad input. */

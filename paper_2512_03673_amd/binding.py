@@ -24,7 +24,8 @@ EXPORTS = ("convrot_status_string", "convrot_version", "convrot_packed_bytes", "
            "convlinear4bit_forward", "convrot_w4a4_gemm_i32",
            "convrot_prepare_weight8", "convrot_rotquant_act8", "convrot_w8a8_gemm_dequant",
            "convlinear8bit_forward", "convrot_w8a8_gemm_i32", "convrot_rotated_absmax",
-           "convrot_workspace_bytes8", "convrot_packed_bytes8", "convrot_unpack_codes")
+           "convrot_workspace_bytes8", "convrot_packed_bytes8", "convrot_unpack_codes",
+           "convrot_gemm_tile_rows")
 
 _lib = None
 
@@ -67,6 +68,8 @@ def load() -> ctypes.CDLL:
     lib.convlinear8bit_forward.argtypes = lib.convlinear4bit_forward.argtypes
     lib.convrot_w8a8_gemm_i32.argtypes = lib.convrot_w4a4_gemm_i32.argtypes
     lib.convrot_rotated_absmax.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+    lib.convrot_gemm_tile_rows.argtypes = [i64, i64]
+    lib.convrot_gemm_tile_rows.restype = i32
     lib.convrot_packed_bytes8.argtypes = [i64, i64]
     lib.convrot_packed_bytes8.restype = sz
     lib.convrot_unpack_codes.argtypes = [vp, i64, i64, vp, vp]
@@ -83,6 +86,10 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return int(load().convrot_version())
+
+
+def gemm_tile_rows(M: int, N: int) -> int:
+    return int(load().convrot_gemm_tile_rows(M, N))
 
 
 def packed_bytes(rows: int, K: int) -> int:

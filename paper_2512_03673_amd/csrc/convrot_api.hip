@@ -62,6 +62,12 @@ const char *convrot_status_string(int status)
 
 int convrot_version(void) { return CONVROT_VERSION; }
 
+int convrot_gemm_tile_rows(int64_t M, int64_t N)
+{
+    if (M < 0 || N < 0) return 0;
+    return convrot::gemm_tile_rows(M, N);
+}
+
 size_t convrot_packed_bytes(int64_t rows, int64_t K)
 {
     if (rows < 0 || K <= 0 || (K & 1)) return 0;

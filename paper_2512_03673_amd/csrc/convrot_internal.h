@@ -6,6 +6,19 @@
 
 namespace convrot {
 
+// Block tile of both GEMM kernels for an [M, N] output: X rows per tile, 192 (with 192 W rows) or 256
+// (with 128).  Blocks are dealt to the 256 compute units as slots free up, so a launch lasts about as
+// long as the busiest unit's share, ceil(tiles / 256) blocks of TM x TN products each; the square tile
+// moves fewer operand bytes per product and takes the ties.
+inline int gemm_tile_rows(int64_t M, int64_t N)
+{
+    auto work = [&](int64_t tm, int64_t tn) {
+        const int64_t tiles = ((M + tm - 1) / tm) * ((N + tn - 1) / tn);
+        return ((tiles + 255) / 256) * tm * tn;
+    };
+    return work(192, 192) <= work(256, 128) ? 192 : 256;
+}
+
 // Rotate + quantise + pack `rows` rows of K bf16 values (group in {4,16,64,256,1024}; bits 4: FP6 E2M3
 // codes in the layout of e2m3_layout.h, bits 8: one int8 per code in the layout of panel_layout.h).
 hipError_t launch_rotquant(const void *X, int64_t rows, int64_t K, int group, int bits, void *Xq, float *scale,

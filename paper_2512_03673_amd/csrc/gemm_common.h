@@ -41,10 +41,13 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0()
 }
 
 // global_load_lds_dwordx4: lane l copies 16 bytes from its global address to LDS address M0 + 16 l.
+// M0 is written here and not named as a clobber: the compiler reserves it (it never keeps a value in M0
+// across instructions, it sets it right before each instruction that reads it), and it rejects reserved
+// registers in clobber lists with a warning.
 __device__ __forceinline__ void lds_dma16(const uint8_t *base, uint32_t lane_off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory", "m0");
+                 :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory");
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 

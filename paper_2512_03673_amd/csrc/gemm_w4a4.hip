@@ -14,10 +14,14 @@
 // codes and 113-135 us on real ones, and a register-only loop sustains 2.7 POP/s of int8 MFMA against
 // 6.6 POP/s of FP6 MFMA on workload-like data.)
 //
-// Data movement.  A block owns a 192 x 192 output tile (4 wavefronts, 96 x 96 each: 3 x 3 accumulator
-// tiles, 144 registers per lane, nine MFMAs on six fragments per K64 step; FLUX's layer widths and token
-// counts are multiples of 192, and the headline shape is exactly three rounds of 512 such tiles) and
-// needs 74 KB of LDS, so that two blocks share a compute unit: while one runs
+// Data movement.  A block of 4 wavefronts (2 x 2) owns an output tile of 384 operand rows per K step,
+// in one of two shapes.  192 x 192 (96 x 96 per wavefront: 3 x 3 accumulator tiles, 144 registers per
+// lane, nine MFMAs on six fragments per K64 step) moves the fewest operand bytes per product; FLUX's
+// layer widths and token counts are multiples of 192, and the headline shape is exactly three rounds of
+// 512 such tiles.  256 x 128 (128 x 64 per wavefront: 4 x 2 accumulator tiles, eight MFMAs on six
+// fragments) has 11 % less work per block, which wins when the grid is no more than a round or two of
+// the chip; the launcher picks by the block count of the busiest compute unit (gemm_tile_rows).
+// Either needs 74 KB of LDS, so that two blocks share a compute unit: while one runs
 // its prologue or epilogue, or waits at a barrier, the other keeps the MFMA pipe busy.  The operands
 // sit in HBM as 3 KB blocks of 32 rows x 128 codes (an A plane of 32 x 64 bytes and a B plane of
 // 32 x 32 bytes, both XOR-swizzled for the fragment reads); a K128 stage of the tile is 12 such blocks
@@ -27,7 +31,7 @@
 //
 // The MFMA's row operand is the W tile and its column operand the X tile, so that a lane ends up
 // with four consecutive n for one m; the epilogue scales, rounds to bf16, transposes through LDS
-// and writes 16 bytes per lane, 128 contiguous bytes per output row.
+// and writes 16 bytes per lane, whole contiguous rows of the wavefront's tile (192 or 128 bytes).
 #include "gemm_common.h"
 
 #include "convrot_internal.h"
@@ -50,29 +54,36 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;                 // 4 wavefronts, 2 x 2
-constexpr int TM = 192, TN = 192;             // block tile
-constexpr int WM = 96, WN = 96;               // wavefront tile
-constexpr int XF = WM / 32, WF = WN / 32;     // fragments (32 rows x one K64 step) per wavefront: 3 of X, 3 of W
-constexpr int kMfmas = XF * WF;               // per K64 step: 9
-constexpr int kBandRows = 8;                  // tile rows per band of the XCD-aware tile order (64 square tiles run per XCD)
-constexpr int NF = XF + WF;
-constexpr int kTileBlocks = (TM + TN) / e2m3::kRows;             // 32-row blocks of a stage: 8 of X, then 4 of W
-constexpr int kAPlane = (TM + TN) * e2m3::kARowBytes;            // LDS stage: A parts, tile row r at r * 64 ... 24 KB
-constexpr int kBPlane = (TM + TN) * e2m3::kBRowBytes;            // ... then B parts, tile row r at r * 32: 12 KB
+constexpr int kTileRows = 384;                // X rows + W rows of a block tile
+constexpr int kTileBlocks = kTileRows / e2m3::kRows;             // 32-row blocks of a stage: those of X, then those of W
+constexpr int kAPlane = kTileRows * e2m3::kARowBytes;            // LDS stage: A parts, tile row r at r * 64 ... 24 KB
+constexpr int kBPlane = kTileRows * e2m3::kBRowBytes;            // ... then B parts, tile row r at r * 32: 12 KB
 constexpr int kStageBytes = kAPlane + kBPlane;                   // 36 KB
 constexpr int kStages = 2;
 constexpr int kRingBytes = kStages * kStageBytes;                // 72 KB
 constexpr int kLoads = kStageBytes / 1024 / 4;                   // 1 KB LDS-direct loads per wavefront per stage: 9
-constexpr int kEpiPitch = WN * 2 + 16;                           // bf16 row of the wavefront tile + pad
-constexpr int kLdsTotal = kRingBytes + (TM + 2 * TN) * 4;        // + the tile's dequantisation scales and bias
 static_assert(kLoads * 4 * 1024 == kStageBytes && kTileBlocks * 3 == kLoads * 4, "stage must split into 1 KB loads over 4 wavefronts");
-static_assert(4 * 32 * kEpiPitch <= kRingBytes, "epilogue staging must fit the ring");
-static_assert(2 * kLdsTotal <= 160 * 1024, "two blocks per compute unit");
-static_assert(NF == 6 && kLoads == 9 && kMfmas == 9, "slot plan of a K64 step");
+
+// Derived constants of a block tile TM x TN (TM + TN = 384, multiples of 64).
+template <int TM_, int TN_>
+struct Tile {
+    static constexpr int TM = TM_, TN = TN_;
+    static constexpr int WM = TM / 2, WN = TN / 2;            // wavefront tile
+    static constexpr int XF = WM / 32, WF = WN / 32;          // fragments (32 rows x one K64 step) per wavefront
+    static constexpr int NF = XF + WF;
+    static constexpr int kMfmas = XF * WF;                    // per K64 step
+    static constexpr int kEpiPitch = WN * 2 + 16;             // bf16 row of the wavefront tile + pad
+    static constexpr int kLdsTotal = kRingBytes + (TM + 2 * TN) * 4;   // + the tile's dequantisation scales and bias
+    static constexpr int kBandRows = TM == TN ? 8 : 6;        // tile rows per band of the XCD-aware tile order
+    static_assert(TM + TN == kTileRows && TM % 64 == 0 && TN % 64 == 0, "tile shape");
+    static_assert(4 * 32 * kEpiPitch <= kRingBytes, "epilogue staging must fit the ring");
+    static_assert(2 * kLdsTotal <= 160 * 1024, "two blocks per compute unit");
+    static_assert(NF == 6 && kLoads == 9 && kMfmas >= 8 && kMfmas <= 9, "slot plan of a K64 step");
+};
 
 }  // namespace
 
-template <bool RAW>
+template <bool RAW, class T>
 __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ x_scale, const uint8_t *__restrict__ Wq,
     const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
@@ -80,6 +91,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    constexpr int TM = T::TM, TN = T::TN, WM = T::WM, WN = T::WN, XF = T::XF, WF = T::WF, NF = T::NF;
+    constexpr int kMfmas = T::kMfmas, kEpiPitch = T::kEpiPitch, kBandRows = T::kBandRows;
 
     int tm, tn;
     if (!tile_of_block<kBandRows>(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
@@ -101,7 +114,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     }
 
     // ---- global -> LDS (direct).  Load j of a stage (0..35) copies kilobyte j % 3 of the 3 KB block of
-    // 32-row group j / 3 of the tile (groups 0..7 are X rows, 8..11 W rows): kilobytes 0, 1 are the A plane
+    // 32-row group j / 3 of the tile (the first TM / 32 groups are X rows, the rest W rows): kilobytes 0, 1 are the A plane
     // (rows 0-15, 16-31), kilobyte 2 the B plane.  Wavefront w issues loads w, w + 4, ...; a group past
     // the operand's last one (edge tiles) re-reads the last one, whose results are never stored.
     const int x_groups = (M + e2m3::kRows - 1) / e2m3::kRows, w_groups = (N + e2m3::kRows - 1) / e2m3::kRows;
@@ -135,7 +148,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
     }
     const int xrow0 = wm0, wrow0 = TM + wn0;   // first tile row of the wavefront's X and W fragments
 
-    v8i op[2][NF];   // [K64 step parity][fragment]: 0..3 X rows 32 f .., 4..5 W rows 32 (f - 4) ..; 6 dwords used
+    v8i op[2][NF];   // [K64 step parity][fragment]: 0..XF-1 X rows 32 f .., then W rows 32 (f - XF) ..; 6 dwords used
     auto read_frag = [&](int s, auto KSI, auto F) {
         constexpr int ks = decltype(KSI)::value, f = decltype(F)::value;
         const uint8_t *sbase = lds + ((unsigned)s % kStages) * kStageBytes;
@@ -158,15 +171,20 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
 
     // One K64 step, slot by slot, in issue order (scheduling barriers pin it): a wavefront issues in
     // order, so every memory instruction gets an MFMA slot of its own instead of queueing up in a burst.
-    //   slot m: MFMA (i = m / 3, j = m % 3: the X fragment stays for three MFMAs, measured 1 % faster than the W
+    //   slot m: MFMA (i = m / WF, j = m % WF: the X fragment stays for WF MFMAs, measured 1 % faster than the W
     //   fragment staying) on the fragments of step KSI;  m < 6: fetch fragment m of the next step (stage ns,
-    //   the other K64 parity);  REFILL: LDS-direct load m of stage rs
+    //   the other K64 parity);  REFILL: LDS-direct load m of stage rs (with eight slots the last takes two)
     auto slot = [&](auto MI, auto KSI, auto REFILL, int ns, int rs) {
         constexpr int m = decltype(MI)::value, ks = decltype(KSI)::value, i = m / WF, j = m % WF;
-        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(op[ks][XF + j], op[ks][i], acc[i][j], 2, 2, 0, 0, 0, 0);
-        if constexpr (decltype(REFILL)::value) load_stage_part(rs, std::integral_constant<int, m>{});
-        if constexpr (m < NF) read_frag(ns, std::integral_constant<int, 1 - ks>{}, std::integral_constant<int, m>{});
-        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (m < kMfmas) {
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(op[ks][XF + j], op[ks][i], acc[i][j], 2, 2, 0, 0, 0, 0);
+            if constexpr (decltype(REFILL)::value) {
+                load_stage_part(rs, std::integral_constant<int, m>{});
+                if constexpr (m == kMfmas - 1 && kMfmas < kLoads) load_stage_part(rs, std::integral_constant<int, kLoads - 1>{});
+            }
+            if constexpr (m < NF) read_frag(ns, std::integral_constant<int, 1 - ks>{}, std::integral_constant<int, m>{});
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
     auto step = [&](auto KSI, auto REFILL, int ns, int rs) {
         __builtin_amdgcn_sched_barrier(0);
@@ -260,9 +278,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
         float sxm[XF];
 #pragma unroll
         for (int i = 0; i < XF; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
-        uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x 96 bf16 staging tile
-        // read-back: 16 lanes per row of 192 bytes, 12 of them active, 4 rows per pass
-        const int rb_row = lane >> 4, rb_piece = lane & 15;
+        uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x WN bf16 staging tile
+        // read-back: a row of WN bf16 is WN / 8 pieces of 16 bytes; 8 lanes per row (8 rows per pass) when
+        // that is 8, else 16 lanes per row, WN / 8 of them active (4 rows per pass)
+        constexpr int kRbLanes = WN / 8 <= 8 ? 8 : 16, kRbRows = 64 / kRbLanes;
+        const int rb_row = lane / kRbLanes, rb_piece = lane % kRbLanes;
         const bool rb_active = rb_piece < WN / 8;
         const int ncol = n0 + wn0 + rb_piece * 8;               // first of this lane's 8 output columns
         auto body = [&](auto INTERIOR, auto BIAS) {
@@ -284,10 +304,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
                         *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
                             make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
                     }
-                // the same wavefront reads back row-contiguous: 12 lanes cover one 192-byte row, 4 rows per pass
+                // the same wavefront reads back row-contiguous
 #pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const int r = it * 4 + rb_row;
+                for (int it = 0; it < 32 / kRbRows; ++it) {
+                    const int r = it * kRbRows + rb_row;
                     if (!rb_active) continue;
                     const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + rb_piece * 16);
                     const int mo = mrow + r;
@@ -320,12 +340,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
 
 namespace {
 
-template <bool RAW>
-hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, const void *bias,
-                      int M, int N, int K,
-                      void *Y, int32_t *acc, hipStream_t stream)
+template <bool RAW, class T>
+hipError_t launch_tile(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, const void *bias,
+                       int M, int N, int K, void *Y, int32_t *acc, hipStream_t stream)
 {
-    const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
+    const int tiles_m = (M + T::TM - 1) / T::TM, tiles_n = (N + T::TN - 1) / T::TN;
     const int ntiles = tiles_m * tiles_n;
     const int grid = ((ntiles + kNumXcd - 1) / kNumXcd) * kNumXcd;
     // The dynamic-LDS limit of a kernel is a per-device setting: raise it once on every device the
@@ -334,15 +353,26 @@ hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, cons
     int dev = 0;
     if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
     if (dev < 0 || dev >= 64 || !attr_done[dev]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4a4_kernel<RAW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w4a4_kernel<RAW, T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsTotal);
         if (e != hipSuccess) return e;
         if (dev >= 0 && dev < 64) attr_done[dev] = true;
     }
-    hipLaunchKernelGGL((gemm_w4a4_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsTotal, stream, (const uint8_t *)Xq,
+    hipLaunchKernelGGL((gemm_w4a4_kernel<RAW, T>), dim3(grid), dim3(kThreads), T::kLdsTotal, stream, (const uint8_t *)Xq,
                        x_scale, (const uint8_t *)Wq, w_scale, (const uint16_t *)bias, M, N, K, (uint16_t *)Y, acc, tiles_m,
                        tiles_n);
     return hipGetLastError();
+}
+
+template <bool RAW>
+hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, const void *bias,
+                      int M, int N, int K, void *Y, int32_t *acc, hipStream_t stream)
+{
+    using Square = Tile<192, 192>;
+    using Tall = Tile<256, 128>;
+    if (gemm_tile_rows(M, N) == Square::TM)
+        return launch_tile<RAW, Square>(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc, stream);
+    return launch_tile<RAW, Tall>(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc, stream);
 }
 
 }  // namespace

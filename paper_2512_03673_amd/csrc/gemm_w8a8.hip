@@ -4,10 +4,14 @@
 //   acc[m,n] = sum_k q_x[m,k] q_w[n,k]        int8 codes in [-127, 127], int32 accumulate, exact
 //   Y[m,n]   = bf16( float(acc) * s_x[m] * s_w[n] + bias[n] )
 //
-// Same structure as the 4-bit kernel in gemm_w4a4.hip (256 x 128 tiles, two blocks per compute unit,
-// LDS-direct loads into a swizzled ring of 3 stages, one memory instruction per MFMA slot, scales and
-// bias parked in LDS, LDS-transposed bf16 epilogue) minus the widening: a 16-byte fragment read from
-// LDS is an operand of v_mfma_i32_32x32x32_i8 as it stands.  A stage is 64 bytes = 64 codes of K per
+// Same shape as the 4-bit kernel in gemm_w4a4.hip (2 x 2 wavefronts per block, two blocks per compute
+// unit, LDS-direct loads into a swizzled ring, one memory instruction per MFMA slot, X fragment
+// stationary, scales and bias parked in LDS, LDS-transposed bf16 epilogue), with a ring of 3 stages of
+// 64 codes of K: a 16-byte fragment read from LDS is an operand of v_mfma_i32_32x32x32_i8 as it stands.
+// Two block tiles of 384 rows per stage are compiled, 192 x 192 (3 x 3 accumulator tiles per wavefront)
+// and 256 x 128 (4 x 2): the square one moves fewer operand bytes per product, the other one has 11 %
+// less work per block, which wins when the grid is a round or two of the chip; the launcher picks by
+// the block count of the busiest compute unit.  A stage is 64 bytes = 64 codes of K per
 // row, i.e. two MFMAs per accumulator tile; the panel layout of the operands (panel_layout.h) pads the
 // last stage with zero codes.  |acc| <= 127^2 K < 2^31 for K <= 65536.
 #include "gemm_common.h"
@@ -31,25 +35,35 @@ using gemm::wait_vmcnt;
 namespace {
 
 constexpr int kThreads = 256;                 // 4 wavefronts, 2 x 2
-constexpr int TM = 256, TN = 128;             // block tile
-constexpr int WM = 128, WN = 64;              // wavefront tile
-constexpr int XF = WM / 32, WF = WN / 32;     // fragments (32 rows x one K64 step) per wavefront: 4 of X, 2 of W
-constexpr int NF = XF + WF;
+constexpr int kTileRows = 384;                // X rows + W rows of a block tile
 constexpr int kStages = 3;
-constexpr int kStageBytes = (TM + TN) * kRowBytes;        // 24 KB
+constexpr int kStageBytes = kTileRows * kRowBytes;        // 24 KB
 constexpr int kRingBytes = kStages * kStageBytes;         // 72 KB
 constexpr int kChunks = kStageBytes / 1024 / 4;           // 1 KB LDS-direct loads per wavefront per stage: 6
-constexpr int kXChunks = TM * kRowBytes / 1024 / 4;       // ... of which the first 4 fetch X rows
-constexpr int kEpiPitch = WN * 2 + 16;                    // bf16 row of the wavefront tile + pad
-constexpr int kLdsTotal = kRingBytes + (TM + 2 * TN) * 4; // + the tile's dequantisation scales and bias
-static_assert(kChunks * 4 * 1024 == kStageBytes, "stage must split into 1 KB chunks over 4 wavefronts");
-static_assert(4 * 32 * kEpiPitch <= kRingBytes, "epilogue staging must fit the ring");
-static_assert(2 * kLdsTotal <= 160 * 1024, "two blocks per compute unit");
-static_assert(kSubSteps == 2 && NF == 6, "slot plan of a step");
+
+// Derived constants of a block tile TM x TN (TM + TN = 384, multiples of 64).
+template <int TM_, int TN_>
+struct Tile {
+    static constexpr int TM = TM_, TN = TN_;
+    static constexpr int WM = TM / 2, WN = TN / 2;            // wavefront tile
+    static constexpr int XF = WM / 32, WF = WN / 32;          // fragments (32 rows x one K32 step) per wavefront
+    static constexpr int NF = XF + WF;
+    static constexpr int kMfmas = XF * WF;                    // per K32 step
+    static constexpr int kXChunks = TM * kRowBytes / 1024 / 4;   // the first of a wavefront's chunks fetch X rows
+    static constexpr int kEpiPitch = WN * 2 + 16;             // bf16 row of the wavefront tile + pad
+    static constexpr int kLdsTotal = kRingBytes + (TM + 2 * TN) * 4;   // + the tile's dequantisation scales and bias
+    static constexpr int kBandRows = TM == TN ? 8 : 6;        // tile rows per band of the tile order
+    static_assert(TM + TN == kTileRows && TM % 64 == 0 && TN % 64 == 0, "tile shape");
+    static_assert(kXChunks * 4 * 16 == TM, "X rows must fill whole chunks of all four wavefronts");
+    static_assert(4 * 32 * kEpiPitch <= kRingBytes, "epilogue staging must fit the ring");
+    static_assert(2 * kLdsTotal <= 160 * 1024, "two blocks per compute unit");
+    static_assert(NF == 6 && kMfmas >= 8 && kMfmas <= 9, "slot plan of a step");
+};
+static_assert(kChunks * 4 * 1024 == kStageBytes && kChunks == 6 && kSubSteps == 2, "slot plan of a step");
 
 }  // namespace
 
-template <bool RAW>
+template <bool RAW, class T>
 __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ x_scale, const uint8_t *__restrict__ Wq,
     const float *__restrict__ w_scale, const uint16_t *__restrict__ bias, int M, int N, int K,
@@ -57,9 +71,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    constexpr int TM = T::TM, TN = T::TN, WM = T::WM, WN = T::WN, XF = T::XF, WF = T::WF, NF = T::NF;
+    constexpr int kMfmas = T::kMfmas, kXChunks = T::kXChunks, kEpiPitch = T::kEpiPitch, kBandRows = T::kBandRows;
 
     int tm, tn;
-    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    if (!tile_of_block<kBandRows>(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int m0 = tm * TM, n0 = tn * TN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
@@ -70,7 +86,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     // the ring) once the loop is over.
     float my_sx = 0.0f, my_sw = 0.0f, my_b = 0.0f;
     if constexpr (!RAW) {
-        if (m0 + tid < M) my_sx = x_scale[m0 + tid];
+        if (tid < TM && m0 + tid < M) my_sx = x_scale[m0 + tid];
         if (tid < TN && n0 + tid < N) {
             my_sw = w_scale[n0 + tid];
             if (bias) my_b = gemm::bf16_to_f32(bias[n0 + tid]);
@@ -78,7 +94,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     }
 
     // ---- global -> LDS (direct): wavefront w fills chunks w, w+4, ... of every stage; chunk c holds
-    // tile rows 16c .. 16c+15 (rows 0..255 are X, 256..383 are W), which is one 1 KB panel of the operand
+    // tile rows 16c .. 16c+15 (rows 0..TM-1 are X, the rest W), which is one 1 KB panel of the operand
     // (panel_layout.h), K-panels of the same rows 1 KB apart; lane l fills slot l & 3 of row l >> 2.
     const uint8_t *xtile = Xq + (int64_t)(m0 / panel::kRows) * KT * panel::kBytes;
     const uint8_t *wtile = Wq + (int64_t)(n0 / panel::kRows) * KT * panel::kBytes;
@@ -109,7 +125,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     const int xslab = wm0 * kRowBytes;
     const int wslab = (TM + wn0) * kRowBytes;
 
-    // fragment f of step ks (32 codes of K) of stage kt: 0..3 X rows 32 f .., 4..5 W rows 32 (f - 4) ..
+    // fragment f of step ks (32 codes of K) of stage kt: 0..XF-1 X rows 32 f .., then W rows 32 (f - XF) ..
     v4i cur[NF], nxt[NF];
     auto read_frag = [&](v4i (&dst)[NF], int kt, int ks, auto F) {
         constexpr int f = decltype(F)::value;
@@ -126,8 +142,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // One step = 8 MFMAs (one per accumulator tile) on the fragments in `cur`, slot by slot, in issue
-    // order (scheduling barriers pin it): slot m runs MFMA (i = m % 4, j = m / 4); m < 6 fetches
+    // One step = XF * WF MFMAs (one per accumulator tile) on the fragments in `cur`, slot by slot, in issue
+    // order (scheduling barriers pin it): slot m runs MFMA (i = m / WF, j = m % WF), the X fragment
+    // staying for WF MFMAs in a row; m < 6 fetches
     // fragment m of the next step (stage nkt, step nks) into `nxt`; with REFILL slots 2..7 also issue
     // the LDS-direct loads of stage rkt.  With SYNC the step opens with the wait for stage nkt (with a
     // ring of three only that stage is in flight) and the block barrier.
@@ -139,16 +156,19 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
             __builtin_amdgcn_sched_barrier(0);
         }
         auto slot = [&](auto MI) {
-            constexpr int m = decltype(MI)::value, i = m % 4, j = m / 4;
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[XF + j], cur[i], acc[i][j], 0, 0, 0);
-            if constexpr (m < NF) read_frag(nxt, nkt, nks, std::integral_constant<int, m>{});
-            if constexpr (decltype(REFILL)::value && m >= 2 && m - 2 < kChunks) load_chunk(rkt, m - 2);
-            __builtin_amdgcn_sched_barrier(0);
+            constexpr int m = decltype(MI)::value, i = m / WF, j = m % WF;
+            if constexpr (m < kMfmas) {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[XF + j], cur[i], acc[i][j], 0, 0, 0);
+                if constexpr (m < NF) read_frag(nxt, nkt, nks, std::integral_constant<int, m>{});
+                if constexpr (decltype(REFILL)::value && m >= 2 && m - 2 < kChunks) load_chunk(rkt, m - 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         };
         slot(std::integral_constant<int, 0>{}); slot(std::integral_constant<int, 1>{});
         slot(std::integral_constant<int, 2>{}); slot(std::integral_constant<int, 3>{});
         slot(std::integral_constant<int, 4>{}); slot(std::integral_constant<int, 5>{});
         slot(std::integral_constant<int, 6>{}); slot(std::integral_constant<int, 7>{});
+        slot(std::integral_constant<int, 8>{});
 #pragma unroll
         for (int f = 0; f < NF; ++f) cur[f] = nxt[f];   // a renaming
     };
@@ -211,7 +231,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
         }
     } else {
         float *sx_lds = reinterpret_cast<float *>(lds + kRingBytes), *sw_lds = sx_lds + TM;
-        sx_lds[tid] = my_sx;
+        if (tid < TM) sx_lds[tid] = my_sx;
         if (tid < TN) {
             sw_lds[tid] = my_sw;
             sw_lds[TN + tid] = my_b;
@@ -220,18 +240,16 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
         // `interior`: the tile lies wholly inside Y and rows of Y are 16-byte multiples, so the stores need
         // no bounds checks (uniform over the block).
         const bool interior = m0 + TM <= M && n0 + TN <= N && (N & 7) == 0;
-        float swn[WF][4][4], sxm[XF];
-#pragma unroll
-        for (int j = 0; j < WF; ++j)
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const float4 v = *reinterpret_cast<const float4 *>(sw_lds + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4);
-                swn[j][rb][0] = v.x; swn[j][rb][1] = v.y; swn[j][rb][2] = v.z; swn[j][rb][3] = v.w;
-            }
+        float sxm[XF];
 #pragma unroll
         for (int i = 0; i < XF; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
-        uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x 64 bf16 staging tile
-        const int ncol = n0 + wn0 + (lane & 7) * 8;              // first of this lane's 8 output columns
+        uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x WN bf16 staging tile
+        // read-back: a row of WN bf16 is WN / 8 pieces of 16 bytes; 8 lanes per row (8 rows per pass) when
+        // that is 8, else 16 lanes per row, WN / 8 of them active (4 rows per pass)
+        constexpr int kRbLanes = WN / 8 <= 8 ? 8 : 16, kRbRows = 64 / kRbLanes;
+        const int rb_row = lane / kRbLanes, rb_piece = lane % kRbLanes;
+        const bool rb_active = rb_piece < WN / 8;
+        const int ncol = n0 + wn0 + rb_piece * 8;               // first of this lane's 8 output columns
         auto body = [&](auto INTERIOR, auto BIAS) {
 #pragma unroll
             for (int i = 0; i < XF; ++i) {
@@ -240,21 +258,23 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
                 for (int j = 0; j < WF; ++j)
 #pragma unroll
                     for (int rb = 0; rb < 4; ++rb) {
-                        float y[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            y[e] = ((float)acc[i][j][rb * 4 + e] * sxm[i]) * swn[j][rb][e];
-                            if constexpr (decltype(BIAS)::value) y[e] += sw_lds[TN + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4 + e];
-                        }
                         const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
+                        const float4 sw = *reinterpret_cast<const float4 *>(sw_lds + wn0 + col);
+                        float y[4] = {((float)acc[i][j][rb * 4 + 0] * sxm[i]) * sw.x, ((float)acc[i][j][rb * 4 + 1] * sxm[i]) * sw.y,
+                                      ((float)acc[i][j][rb * 4 + 2] * sxm[i]) * sw.z, ((float)acc[i][j][rb * 4 + 3] * sxm[i]) * sw.w};
+                        if constexpr (decltype(BIAS)::value) {
+                            const float4 b = *reinterpret_cast<const float4 *>(sw_lds + TN + wn0 + col);
+                            y[0] += b.x; y[1] += b.y; y[2] += b.z; y[3] += b.w;
+                        }
                         *reinterpret_cast<uint2 *>(stage + (lane & 31) * kEpiPitch + col * 2) =
                             make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
                     }
-                // the same wavefront reads back row-contiguous: 8 lanes cover one 128-byte row, 8 rows per pass
+                // the same wavefront reads back row-contiguous
 #pragma unroll
-                for (int it = 0; it < 4; ++it) {
-                    const int r = it * 8 + (lane >> 3);
-                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + (lane & 7) * 16);
+                for (int it = 0; it < 32 / kRbRows; ++it) {
+                    const int r = it * kRbRows + rb_row;
+                    if (!rb_active) continue;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + rb_piece * 16);
                     const int mo = mrow + r;
                     uint16_t *dst = Y + (int64_t)mo * N + ncol;
                     if constexpr (decltype(INTERIOR)::value) {
@@ -285,12 +305,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
 
 namespace {
 
-template <bool RAW>
-hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, const void *bias,
-                      int M, int N, int K,
-                      void *Y, int32_t *acc, hipStream_t stream)
+template <bool RAW, class T>
+hipError_t launch_tile(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, const void *bias,
+                       int M, int N, int K, void *Y, int32_t *acc, hipStream_t stream)
 {
-    const int tiles_m = (M + TM - 1) / TM, tiles_n = (N + TN - 1) / TN;
+    const int tiles_m = (M + T::TM - 1) / T::TM, tiles_n = (N + T::TN - 1) / T::TN;
     const int ntiles = tiles_m * tiles_n;
     const int grid = ((ntiles + kNumXcd - 1) / kNumXcd) * kNumXcd;
     // The dynamic-LDS limit of a kernel is a per-device setting: raise it once on every device the
@@ -299,15 +318,26 @@ hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, cons
     int dev = 0;
     if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
     if (dev < 0 || dev >= 64 || !attr_done[dev]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w8a8_kernel<RAW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w8a8_kernel<RAW, T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsTotal);
         if (e != hipSuccess) return e;
         if (dev >= 0 && dev < 64) attr_done[dev] = true;
     }
-    hipLaunchKernelGGL((gemm_w8a8_kernel<RAW>), dim3(grid), dim3(kThreads), kLdsTotal, stream, (const uint8_t *)Xq,
+    hipLaunchKernelGGL((gemm_w8a8_kernel<RAW, T>), dim3(grid), dim3(kThreads), T::kLdsTotal, stream, (const uint8_t *)Xq,
                        x_scale, (const uint8_t *)Wq, w_scale, (const uint16_t *)bias, M, N, K, (uint16_t *)Y, acc, tiles_m,
                        tiles_n);
     return hipGetLastError();
+}
+
+template <bool RAW>
+hipError_t launch_one(const void *Xq, const float *x_scale, const void *Wq, const float *w_scale, const void *bias,
+                      int M, int N, int K, void *Y, int32_t *acc, hipStream_t stream)
+{
+    using Square = Tile<192, 192>;
+    using Tall = Tile<256, 128>;
+    if (gemm_tile_rows(M, N) == Square::TM)
+        return launch_tile<RAW, Square>(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc, stream);
+    return launch_tile<RAW, Tall>(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc, stream);
 }
 
 }  // namespace

@@ -28,7 +28,7 @@ def declared_symbols():
 def test_header_symbols_are_exported(lib):
     from paper_2512_03673_amd import binding
     names = declared_symbols()
-    assert len(names) == 18
+    assert len(names) == 19
     assert sorted(binding.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -36,7 +36,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_size_queries_and_strings(lib):
     from paper_2512_03673_amd import binding as b
-    assert b.version() == 400
+    assert b.version() == 401
     # 4-bit code matrices: 3 KB blocks of 32 rows x 128 codes (6 bits per code), rows and K padded up to whole blocks
     assert b.packed_bytes(4608, 3072) == 4608 * 3072 * 3 // 4
     assert b.packed_bytes(37, 96) == 2 * 1 * 3072 and b.packed_bytes(3, 32) == 3072
@@ -54,6 +54,17 @@ def test_size_queries_and_strings(lib):
     assert b.status_string(0) == "ok"
     assert "group" in b.status_string(-3)
     assert b.status_string(-99) == "unknown status"
+
+
+def test_gemm_tile_choice(lib):
+    from paper_2512_03673_amd import binding as b
+    # up to 256 tiles of either shape the smaller tile (256 x 128) has less work per block
+    assert b.gemm_tile_rows(256, 1024) == 256 and b.gemm_tile_rows(4608, 3072) == 256
+    # 256 square tiles against 288 of the other shape: one block per compute unit against two
+    assert b.gemm_tile_rows(3072, 3072) == 192 and b.gemm_tile_rows(3001, 3070) == 192
+    # headline shape: 1536 square tiles (6 per unit) against 1728 (7 per unit)
+    assert b.gemm_tile_rows(4608, 12288) == 192
+    assert b.gemm_tile_rows(-1, 5) == 0 and b.gemm_tile_rows(5, -1) == 0
 
 
 def test_argument_validation_without_a_device(lib):

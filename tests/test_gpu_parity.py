@@ -130,6 +130,21 @@ def test_gemm_i32_bit_exact(cr, M, N, K):
     assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
 
 
+@pytest.mark.parametrize("M,N,K", [(3072, 3072, 128), (3001, 3070, 160)])
+def test_gemm_i32_bit_exact_on_square_tiles(cr, M, N, K):
+    # The shapes above all take the 256 x 128 block tile (at most 256 tiles of either shape); these take the
+    # 192 x 192 one: 256 square tiles against 288, whole and with ragged edges in both directions.
+    assert cr.gemm_tile_rows(M, N) == 192 and cr.gemm_tile_rows(300, 520) == 256
+    rng = np.random.default_rng(M + N + K)
+    qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    qx[0, :] = 7
+    qw[0, :] = -7
+    acc = cr.convrot_w4a4_gemm_i32(codes4_to_dev(qx), codes4_to_dev(qw), M, N, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
+
+
 def test_gemm_i32_small_products_after_a_large_partial_sum(cr):
     # The GEMM accumulates in fp32, exactly as long as no partial sum needs more than 24 bits.  The hardest
     # case for that: a partial sum near the bound (49 * 60000 = 2.94e6), then thousands of products of +-1,
@@ -190,6 +205,34 @@ def test_gemm_dequant_with_bias(cr, M, N, K):
     mag = np.maximum(np.abs(bits_to_f64(yo)), np.abs(bits_to_f64(bias))[None, :])
     assert (err <= mag * 2.0 ** -7).all()
     check_output(yb, yo, "dequant+bias")
+
+
+@pytest.mark.parametrize("M,N,K", [(3001, 3070, 96), (3072, 3067, 224)])
+def test_gemm_dequant_with_bias_on_square_tiles(cr, M, N, K):
+    # the 192 x 192 block tile's epilogue: interior tiles, ragged rows, and rows of Y that are not 16-byte multiples
+    assert cr.gemm_tile_rows(M, N) == 192
+    rng = np.random.default_rng(M * N + K)
+    qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    sx = np.exp(rng.uniform(-6, 2, M)).astype(np.float32)
+    sw = np.exp(rng.uniform(-9, -4, N)).astype(np.float32)
+    bias = wl.f32_to_bf16_bits((rng.standard_normal(N) * 0.5).astype(np.float32))
+    xq, wq = codes4_to_dev(qx), codes4_to_dev(qw)
+    acc = oracle.int_gemm(qx, qw)
+    y = cr.convrot_w4a4_gemm_dequant(xq, torch.from_numpy(sx).cuda(), wq, torch.from_numpy(sw).cuda(), K)
+    torch.cuda.synchronize()
+    yb, yo = bf16_to_host_bits(y), oracle.dequant(acc, sx, sw)
+    d = bf16_ulp_diff(yb, yo)
+    assert d.max() <= 1 and (d == 0).mean() > 0.999
+    y = cr.convrot_w4a4_gemm_dequant(xq, torch.from_numpy(sx).cuda(), wq, torch.from_numpy(sw).cuda(), K,
+                                     bias=to_dev_bf16(bias))
+    torch.cuda.synchronize()
+    yb, yo = bf16_to_host_bits(y), oracle.dequant(acc, sx, sw, bias)
+    assert (bf16_ulp_diff(yb, yo) == 0).mean() > 0.995
+    err = np.abs(bits_to_f64(yb) - bits_to_f64(yo))
+    mag = np.maximum(np.abs(bits_to_f64(yo)), np.abs(bits_to_f64(bias))[None, :])
+    assert (err <= mag * 2.0 ** -7).all()
+    check_output(yb, yo, "dequant+bias, square tiles")
 
 
 def test_forward_with_bias_matches_oracle(cr):

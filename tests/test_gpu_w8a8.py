@@ -75,6 +75,34 @@ def test_gemm8_i32_bit_exact(cr, M, N, K):
     assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
 
 
+@pytest.mark.parametrize("M,N,K", [(3072, 3072, 64), (3001, 3067, 160)])
+def test_gemm8_on_square_tiles(cr, M, N, K):
+    # The shapes above all take the 256 x 128 block tile (at most 256 tiles of either shape); these take the
+    # 192 x 192 one, whole and with ragged edges: raw accumulators bit-exact, then the dequantising epilogue.
+    assert cr.gemm_tile_rows(M, N) == 192 and cr.gemm_tile_rows(300, 520) == 256
+    rng = np.random.default_rng(M + N + K)
+    qx = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    qw = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    qx[0, :] = 127
+    qw[0, :] = -127
+    xq, wq = codes8_to_dev(qx), codes8_to_dev(qw)
+    ref = oracle.int_gemm(qx, qw)
+    acc = cr.convrot_w8a8_gemm_i32(xq, wq, M, N, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), ref)
+    sx = np.exp(rng.uniform(-6, 2, M)).astype(np.float32)
+    sw = np.exp(rng.uniform(-9, -4, N)).astype(np.float32)
+    bias = wl.f32_to_bf16_bits((rng.standard_normal(N) * 0.5).astype(np.float32))
+    y = cr.convrot_w8a8_gemm_dequant(xq, torch.from_numpy(sx).cuda(), wq, torch.from_numpy(sw).cuda(), K)
+    torch.cuda.synchronize()
+    d = bf16_ulp_diff(bf16_to_host_bits(y), oracle.dequant(ref, sx, sw))
+    assert d.max() <= 1 and (d == 0).mean() > 0.999
+    y = cr.convrot_w8a8_gemm_dequant(xq, torch.from_numpy(sx).cuda(), wq, torch.from_numpy(sw).cuda(), K,
+                                     bias=to_dev_bf16(bias))
+    torch.cuda.synchronize()
+    check_output(bf16_to_host_bits(y), oracle.dequant(ref, sx, sw, bias), "dequant8+bias, square tiles")
+
+
 @pytest.mark.parametrize("M,N,K,with_bias", [(300, 520, 1024, False), (129, 1026, 3072, True), (31, 5, 64, True)])
 def test_gemm8_dequant_on_identical_codes(cr, M, N, K, with_bias):
     rng = np.random.default_rng(M + N + K)
