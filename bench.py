@@ -31,8 +31,8 @@ I8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA, published (the figure th
 # dispatch), each scaled by what the same counter reads for a plain copy of known size (x2.0 and
 # x1.0); the runs are in profiles/gemm_w4a4_and_rotquant_headline_hbm_traffic_and_mfma_busy.md.
 # These are stored measurements of this build, not taken live (bench.py cannot run the profiler on itself).
-MEASURED_TRAFFIC_BYTES = {"gemm_w4a4_kernel": 83173 * 1024 * 2.0 + 110597 * 1024 * 1.0,
-                          "rotquant_kernel": 14075 * 1024 * 2.0 + 10515 * 1024 * 1.0}
+MEASURED_TRAFFIC_BYTES = {"gemm_w4a4_kernel": 83183 * 1024 * 2.0 + 110595 * 1024 * 1.0,
+                          "rotquant_kernel": 14079 * 1024 * 2.0 + 10515 * 1024 * 1.0}
 COPY_BYTES = 512 << 20       # size of the calibration copy (--calibrate-copy)
 COLD_FOOTPRINT = 768 << 20   # kernel A, cold: bytes touched between two uses of one buffer set
 
