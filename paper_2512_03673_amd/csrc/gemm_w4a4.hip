@@ -345,6 +345,7 @@ hipError_t launch_tile(const void *Xq, const float *x_scale, const void *Wq, con
                        int M, int N, int K, void *Y, int32_t *acc, hipStream_t stream)
 {
     const int tiles_m = (M + T::TM - 1) / T::TM, tiles_n = (N + T::TN - 1) / T::TN;
+    if ((int64_t)tiles_m * tiles_n > (1 << 30)) return hipErrorInvalidValue;   // the kernel counts tiles in 32 bits
     const int ntiles = tiles_m * tiles_n;
     const int grid = ((ntiles + kNumXcd - 1) / kNumXcd) * kNumXcd;
     // The dynamic-LDS limit of a kernel is a per-device setting: raise it once on every device the
