@@ -18,8 +18,10 @@
  *   - Pointers named in the comments as DEVICE are device (HBM) pointers; everything else is
  *     passed by value.  All matrices are row-major and contiguous.  bf16 is the raw 16-bit
  *     pattern.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *   - Calls are asynchronous on `stream`; they allocate and free nothing and keep no state.
- *     The caller owns every buffer, including the workspace, for the duration of the work.
+ *   - Calls are asynchronous on `stream`; they allocate and free nothing and keep no state: a
+ *     call depends on its arguments only and may be the first call of a process, also under
+ *     stream capture.  The caller owns every buffer, including the workspace, for the duration
+ *     of the work.
  *   - Inputs are never written.  Outputs must not alias inputs.
  *   - Return value: CONVROT_OK (0) or a negative convrot_status.  Arguments are validated on
  *     the host before any launch: on an argument error nothing is launched and no output byte
@@ -46,9 +48,11 @@
  *   matrix  block (R, S) - rows 32 R .., codes 128 S .. - at (R * ceil(K / 128) + S) * 3072
  *
  * i.e. ceil(rows / 32) * ceil(K / 128) * 3072 bytes (convrot_packed_bytes).  The codes of the last
- * block of a row past K are written as zeros by the producing call, the rows past `rows` of the
- * last row block are never read or written (a caller that fills a code matrix itself must zero
- * that K padding too).  (8-bit variant: one int8 in [-127, 127] per code, K bytes per row, stored
+ * block of a row past K are written as zeros by the producing call (a caller that fills a code
+ * matrix itself must zero that K padding too).  The rows past `rows` of the last row block are never
+ * written; the GEMM does load them along with the rest of the 3 KB block, but their products only
+ * reach accumulators of rows that are not stored (every six-bit pattern is a finite number and rows
+ * are independent), so their contents do not matter and need no initialisation.  (8-bit variant: one int8 in [-127, 127] per code, K bytes per row, stored
  * as 1 KB panels of 16 rows x 64 bytes, the K-panels of the same 16 rows adjacent: byte b of row r
  * at ((r / 16) * KP + b / 64) * 1024 + (r % 16) * 64 + b % 64, KP = ceil(K / 64), same padding
  * rules; convrot_packed_bytes8.)  Both layouts exist so that the GEMM's loads are whole contiguous

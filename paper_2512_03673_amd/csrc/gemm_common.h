@@ -18,9 +18,6 @@ constexpr int kRowBytes = 64;                 // bytes of K per row per stage: 1
 constexpr int kSubSteps = kRowBytes / 32;     // MFMA K-steps of 32 bytes per row (one ds_read_b128 per fragment) per stage
 constexpr int kNumXcd = 8;
 
-__device__ __forceinline__ uint32_t nib_lo(uint32_t p) { return (p << 4) & 0xF0F0F0F0u; }
-__device__ __forceinline__ uint32_t nib_hi(uint32_t p) { return p & 0xF0F0F0F0u; }
-
 // Which of the four 16-byte slots of its LDS row a piece lands in: slot = piece ^ swz(row).
 // For any 8 consecutive rows the (row & 1, slot) pairs are distinct (32 banks), and for any 16
 // consecutive rows the (row & 3, slot) pairs are distinct (64 banks).
@@ -41,9 +38,14 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0()
 }
 
 // global_load_lds_dwordx4: lane l copies 16 bytes from its global address to LDS address M0 + 16 l.
-// M0 is written here and not named as a clobber: the compiler reserves it (it never keeps a value in M0
-// across instructions, it sets it right before each instruction that reads it), and it rejects reserved
-// registers in clobber lists with a warning.
+// M0 is written here and not named as a clobber.  This relies on a property of the AMDGPU backend, not on a
+// documented contract: M0 is a reserved register that the register allocator never assigns a value to; every
+// instruction the backend itself emits that reads M0 (LDS-direct loads from the builtin, s_movrel, GWS, s_sendmsg)
+// is preceded by its own write in the same block.  Naming a reserved register in a clobber list is rejected with
+// a warning ("may not be preserved ... may lead to undefined behaviour") and changes nothing in the generated code,
+// so it would only look like a guarantee.  None of the instructions above occurs in the GEMM kernels besides this
+// one (the build prints the hipcc version it ran with, and the bit-exact GEMM tests are the check that a new
+// toolchain still behaves so: a stale M0 sends a kilobyte of operands to the wrong place in the ring).
 __device__ __forceinline__ void lds_dma16(const uint8_t *base, uint32_t lane_off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"

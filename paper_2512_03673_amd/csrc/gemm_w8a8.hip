@@ -70,7 +70,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w8a8_kernel(
     uint16_t *__restrict__ Y,
     int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
 {
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    // Statically sized: above 64 KB a dynamic allocation would need a per-device function attribute set
+    // from the host before the first launch, i.e. hidden library state; a static one needs nothing.
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[T::kLdsTotal];
     constexpr int TM = T::TM, TN = T::TN, WM = T::WM, WN = T::WN, XF = T::XF, WF = T::WF, NF = T::NF;
     constexpr int kMfmas = T::kMfmas, kXChunks = T::kXChunks, kEpiPitch = T::kEpiPitch, kBandRows = T::kBandRows;
 
@@ -313,18 +315,7 @@ hipError_t launch_tile(const void *Xq, const float *x_scale, const void *Wq, con
     if ((int64_t)tiles_m * tiles_n > (1 << 30)) return hipErrorInvalidValue;   // the kernel counts tiles in 32 bits
     const int ntiles = tiles_m * tiles_n;
     const int grid = ((ntiles + kNumXcd - 1) / kNumXcd) * kNumXcd;
-    // The dynamic-LDS limit of a kernel is a per-device setting: raise it once on every device the
-    // library launches on (idempotent; a race only repeats it).
-    static bool attr_done[64] = {};
-    int dev = 0;
-    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64 || !attr_done[dev]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_w8a8_kernel<RAW, T>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsTotal);
-        if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < 64) attr_done[dev] = true;
-    }
-    hipLaunchKernelGGL((gemm_w8a8_kernel<RAW, T>), dim3(grid), dim3(kThreads), T::kLdsTotal, stream, (const uint8_t *)Xq,
+    hipLaunchKernelGGL((gemm_w8a8_kernel<RAW, T>), dim3(grid), dim3(kThreads), 0, stream, (const uint8_t *)Xq,
                        x_scale, (const uint8_t *)Wq, w_scale, (const uint16_t *)bias, M, N, K, (uint16_t *)Y, acc, tiles_m,
                        tiles_n);
     return hipGetLastError();

@@ -152,6 +152,8 @@ HEADLINE = CONFIGS["cfg3_mlp"][0]
 # Sec. B: X [1 x 4608 x 15360], W [3072 x 15360]), run with a bias.
 NEXT_CONFIGS: Dict[str, Tuple[LayerSpec, ...]] = {
     "n1_fused_width": (_flux("fused_out", 4608, 15360, 3072, x_kind="halfnormal"),),
+    # the same layer at the group size the paper uses for its high-outlier layers (Sec. 5.2: N_0 = 1024)
+    "n3_group_1024": (_flux("fused_out_g1024", 4608, 15360, 3072, group=1024, x_kind="halfnormal"),),
 }
 
 

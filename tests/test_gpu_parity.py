@@ -130,10 +130,13 @@ def test_gemm_i32_bit_exact(cr, M, N, K):
     assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
 
 
-@pytest.mark.parametrize("M,N,K", [(3072, 3072, 128), (3001, 3070, 160)])
+@pytest.mark.parametrize("M,N,K", [(3072, 3072, 128), (3001, 3070, 160), (3072, 3072, 3072), (3001, 3070, 1056),
+                                   (3072, 3072, 384), (3001, 3070, 512)])
 def test_gemm_i32_bit_exact_on_square_tiles(cr, M, N, K):
     # The shapes above all take the 256 x 128 block tile (at most 256 tiles of either shape); these take the
-    # 192 x 192 one: 256 square tiles against 288, whole and with ragged edges in both directions.
+    # 192 x 192 one: 256 square tiles against 288, whole and with ragged edges in both directions.  K = 128 and
+    # 160 are one and two K128 stages (the pipeline's prologue and drain only); K = 384, 512, 1056 and 3072 are 3, 4,
+    # 9 (the last one padded) and 24 stages, which run the steady-state loop that refills the ring.
     assert cr.gemm_tile_rows(M, N) == 192 and cr.gemm_tile_rows(300, 520) == 256
     rng = np.random.default_rng(M + N + K)
     qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)

@@ -4,6 +4,10 @@ and a forward can be captured into a HIP graph and replayed (it allocates nothin
 The expected outputs are the library's own results on the default stream, which the parity tests hold
 against the oracle; one case here is checked against the oracle directly as well.
 """
+import os
+import subprocess
+import sys
+
 import numpy as np
 import pytest
 import torch
@@ -90,7 +94,6 @@ def test_forward_in_a_hip_graph(cr, bits):
     bias = to_dev_bf16(wl.make_bias(spec))
     Y = torch.zeros((spec.M, spec.N), dtype=torch.bfloat16, device="cuda")
     wsb = torch.empty((wsbytes(spec.M, spec.K),), dtype=torch.uint8, device="cuda")
-    y_eager = fwd(X, wq, ws, 16, bias=bias).clone()     # also the first launch: sets the kernels' LDS limits
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
@@ -107,3 +110,49 @@ def test_forward_in_a_hip_graph(cr, bits):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(Y, y_eager), f"replay {rep}"
+
+
+_FIRST_CALL_CAPTURED = r"""
+import sys
+import torch
+sys.path.insert(0, sys.argv[1])
+from paper_2512_03673_amd import binding as cr
+bits = int(sys.argv[2])
+fwd, packed, wsbytes = ((cr.convlinear4bit_forward, cr.packed_bytes, cr.workspace_bytes) if bits == 4 else
+                        (cr.convlinear8bit_forward, cr.packed_bytes8, cr.workspace_bytes8))
+M, K, N, g = 520, 1024, 3000, 16
+torch.manual_seed(3)
+X = torch.randn((M, K), device="cuda").to(torch.bfloat16)
+# any bytes are a valid code matrix (every six-bit pattern is a finite E2M3 number, every byte an int8 code), so the
+# weight needs no library call; the K padding must hold zero codes, and K = 1024 has none
+wq = torch.randint(0, 256, (packed(N, K),), dtype=torch.uint8, device="cuda")
+ws = torch.rand((N,), device="cuda") * 1e-3 + 1e-4
+bias = torch.randn((N,), device="cuda").to(torch.bfloat16)
+Y = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+wsb = torch.empty((wsbytes(M, K),), dtype=torch.uint8, device="cuda")
+torch.cuda.synchronize()
+graph = torch.cuda.CUDAGraph()
+with torch.cuda.graph(graph):                       # the first call into the library in this process
+    fwd(X, wq, ws, g, Y, wsb, bias=bias)
+for rep in range(3):
+    X.copy_(torch.randn((M, K), device="cuda").to(torch.bfloat16) * (rep + 1))
+    Y.zero_()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    y_eager = fwd(X, wq, ws, g, bias=bias)
+    torch.cuda.synchronize()
+    assert torch.isfinite(Y.float()).all() and Y.float().abs().max() > 0
+    assert torch.equal(Y, y_eager), f"replay {rep}"
+print("first call captured: ok")
+"""
+
+
+@pytest.mark.parametrize("bits", (4, 8))
+def test_first_library_call_of_a_process_under_capture(bits):
+    # The library keeps no set-up for a first eager call to do: a process whose very first call into it is made
+    # under stream capture gets a working graph.  Run in a child process, which has not touched the library.
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", _FIRST_CALL_CAPTURED, root, str(bits)], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode == 0 and "first call captured: ok" in r.stdout, r.stdout + r.stderr

@@ -75,10 +75,13 @@ def test_gemm8_i32_bit_exact(cr, M, N, K):
     assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
 
 
-@pytest.mark.parametrize("M,N,K", [(3072, 3072, 64), (3001, 3067, 160)])
+@pytest.mark.parametrize("M,N,K", [(3072, 3072, 64), (3001, 3067, 160), (3072, 3072, 3072), (3001, 3070, 1056),
+                                   (3001, 3067, 256)])
 def test_gemm8_on_square_tiles(cr, M, N, K):
     # The shapes above all take the 256 x 128 block tile (at most 256 tiles of either shape); these take the
     # 192 x 192 one, whole and with ragged edges: raw accumulators bit-exact, then the dequantising epilogue.
+    # K = 64 and 160 stay inside the ring's prologue; K = 256, 1056 and 3072 are 4, 17 (the last one padded) and 48
+    # stages of 64 codes, which run the steady-state loop that refills the ring.
     assert cr.gemm_tile_rows(M, N) == 192 and cr.gemm_tile_rows(300, 520) == 256
     rng = np.random.default_rng(M + N + K)
     qx = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
