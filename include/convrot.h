@@ -18,10 +18,11 @@
  *   - Pointers named in the comments as DEVICE are device (HBM) pointers; everything else is
  *     passed by value.  All matrices are row-major and contiguous.  bf16 is the raw 16-bit
  *     pattern.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *   - Calls are asynchronous on `stream`; they allocate and free nothing and keep no state: a
- *     call depends on its arguments only and may be the first call of a process, also under
- *     stream capture.  The caller owns every buffer, including the workspace, for the duration
- *     of the work.
+ *   - Calls are asynchronous on `stream`; they allocate and free nothing.  The caller owns every
+ *     buffer, including the workspace, for the duration of the work.  The library keeps no state
+ *     between calls except what convrot_init / convlinear4bit_forward_noalloc describe below (the
+ *     per-device address of one static device array, looked up once); every other call depends on
+ *     its arguments only and may be the first call of a process, also under stream capture.
  *   - Inputs are never written.  Outputs must not alias inputs.
  *   - Return value: CONVROT_OK (0) or a negative convrot_status.  Arguments are validated on
  *     the host before any launch: on an argument error nothing is launched and no output byte
@@ -72,7 +73,7 @@
 extern "C" {
 #endif
 
-#define CONVROT_VERSION 401          /* major*10000 + minor*100 + patch */
+#define CONVROT_VERSION 500          /* major*10000 + minor*100 + patch */
 #define CONVROT_MAX_K 65536          /* longest row the single-pass rotate+quantise kernel holds on chip */
 
 typedef enum convrot_status {
@@ -90,6 +91,17 @@ const char *convrot_status_string(int status);
 
 /* Host.  CONVROT_VERSION of the loaded library. */
 int convrot_version(void);
+
+/*
+ * Host.  Set-up of convlinear4bit_forward_noalloc for the calling thread's current device: looks up the
+ * device address of that call's static workspace (which loads the library's device code onto the device if
+ * no kernel of it has run there yet).  Idempotent, thread-safe, allocates nothing itself: the array is part of
+ * the library's device code and stays resident on a device from the moment that code is loaded until the
+ * process ends.  Optional - convlinear4bit_forward_noalloc does the same on its first call on a device - but
+ * that first call, or this one, must be made outside stream capture.  No other entry point needs it.
+ * CONVROT_ERR_HIP when there is no usable device.
+ */
+int convrot_init(void);
 
 /* Host.  X rows per block tile that both GEMM kernels use for an [M, N] output: 192 (tile 192 x 192) or
  * 256 (tile 256 x 128); 0 when M or N < 0.  The result of the GEMM does not depend on it; the query
@@ -152,6 +164,27 @@ int convrot_w4a4_gemm_dequant(const void *Xq, const float *x_scale, const void *
 int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16,
                            int64_t M, int64_t N, int64_t K, int group, void *Y_bf16,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * convlinear4bit_forward for callers that cannot allocate device memory at all and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical output; the activation codes and scales go to a static device
+ * array of CONVROT_NOALLOC_WORKSPACE_BYTES (64 MiB) inside the library instead of a caller's workspace, and
+ * the call (like every call of this library) invokes no hipMalloc / hipFree and no allocating routine.
+ *   - Limit: convrot_workspace_bytes(M, K) <= CONVROT_NOALLOC_WORKSPACE_BYTES, i.e. about M * K <= 89e6 codes
+ *     (4608 x 15360, the widest FLUX layer at 1024 x 1024 pixels, needs 53 MB); CONVROT_ERR_WORKSPACE beyond
+ *     it, with nothing launched.
+ *   - The array belongs to the device: every call on one GPU uses the same memory and finds the previous
+ *     call's contents there (nothing needs clearing: each call overwrites all it reads).  Calls whose work
+ *     overlaps in time on one GPU - different streams, or graph replays running concurrently - race on it;
+ *     serialise them or use convlinear4bit_forward with separate workspaces.
+ *   - The device used is the calling thread's current device, which must be the device of `stream`.  The
+ *     array's address is looked up on the first call on a device (or by convrot_init); make that first
+ *     call, or convrot_init, outside stream capture.
+ */
+#define CONVROT_NOALLOC_WORKSPACE_BYTES (64u << 20)
+int convlinear4bit_forward_noalloc(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16,
+                                   int64_t M, int64_t N, int64_t K, int group, void *Y_bf16, void *stream);
 
 /*
  * Gate / debug export, not a hot-path call: the raw integer accumulators of the GEMM stage

@@ -25,7 +25,8 @@ EXPORTS = ("convrot_status_string", "convrot_version", "convrot_packed_bytes", "
            "convrot_prepare_weight8", "convrot_rotquant_act8", "convrot_w8a8_gemm_dequant",
            "convlinear8bit_forward", "convrot_w8a8_gemm_i32", "convrot_rotated_absmax",
            "convrot_workspace_bytes8", "convrot_packed_bytes8", "convrot_unpack_codes",
-           "convrot_gemm_tile_rows")
+           "convrot_gemm_tile_rows", "convrot_init", "convlinear4bit_forward_noalloc")
+NOALLOC_WORKSPACE_BYTES = 64 << 20
 
 _lib = None
 
@@ -74,7 +75,11 @@ def load() -> ctypes.CDLL:
     lib.convrot_packed_bytes8.restype = sz
     lib.convrot_unpack_codes.argtypes = [vp, i64, i64, vp, vp]
     lib.convrot_unpack_codes.restype = i32
-    for name in EXPORTS[4:-3]:
+    lib.convrot_init.argtypes = []
+    lib.convrot_init.restype = i32
+    lib.convlinear4bit_forward_noalloc.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
+    lib.convlinear4bit_forward_noalloc.restype = i32
+    for name in EXPORTS[4:15]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -86,6 +91,11 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return int(load().convrot_version())
+
+
+def init() -> None:
+    """convrot_init on torch's current device: loads the device code, resolves the static workspace."""
+    _check(load().convrot_init(), "convrot_init")
 
 
 def gemm_tile_rows(M: int, N: int) -> int:
@@ -219,6 +229,21 @@ def convlinear4bit_forward(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Ten
     _check(load().convlinear4bit_forward(_ptr(X), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K, group, _ptr(Y),
                                          _ptr(workspace), workspace.numel(), _stream(stream)),
            "convlinear4bit_forward")
+    return Y
+
+
+def convlinear4bit_forward_noalloc(X: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor, group: int,
+                                   Y: torch.Tensor, bias: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """As convlinear4bit_forward, the activation codes in the library's static device array; `Y` is the caller's."""
+    _dev(X, torch.bfloat16, "X"); _dev(w_scale, torch.float32, "w_scale"); _dev(Y, torch.bfloat16, "Y")
+    M, K = X.shape
+    N = w_scale.shape[0]
+    if Y.shape != (M, N):
+        raise ValueError("Y: need shape [M, N]")
+    _codes(Wq, packed_bytes(N, K), "Wq")
+    _bias(bias, N)
+    _check(load().convlinear4bit_forward_noalloc(_ptr(X), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K, group,
+                                                 _ptr(Y), _stream(stream)), "convlinear4bit_forward_noalloc")
     return Y
 
 

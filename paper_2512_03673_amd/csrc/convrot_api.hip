@@ -2,6 +2,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "convrot.h"
 #include "convrot_internal.h"
 #include "e2m3_layout.h"
@@ -42,6 +45,50 @@ int check_gemm(const void *Xq, const void *Wq, int64_t M, int64_t N, int64_t K, 
 
 inline int from_hip(hipError_t e) { return e == hipSuccess ? CONVROT_OK : CONVROT_ERR_HIP; }
 
+// ---- the static workspace of convlinear4bit_forward_noalloc.  Every device the library's code is loaded
+// on holds its own copy of this array at its own address, until the process ends.  In host code the
+// name `scratch` is only a handle for hipGetSymbolAddress: the device address it yields (per device)
+// is what kernels get.
+static __device__ __align__(256) uint8_t scratch[CONVROT_NOALLOC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<uint8_t *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the calling thread's current device (resolved once per device).
+int scratch_of_current_device(uint8_t **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CONVROT_ERR_HIP;
+    uint8_t *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            void *q = nullptr;
+            if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return CONVROT_ERR_HIP;
+            p = static_cast<uint8_t *>(q);
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return CONVROT_OK;
+}
+
+// Argument checks shared by the fused forward calls (everything but the workspace).
+int check_forward(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16, int64_t M, int64_t N,
+                  int64_t K, int group, const void *Y_bf16)
+{
+    if (int rc = check_group(group)) return rc;
+    if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
+    if (int rc = check_k(K)) return rc;
+    if (K % group != 0) return CONVROT_ERR_SHAPE;
+    if (missing(X_bf16, M) || missing(Wq, N) || missing(w_scale, N) || missing(Y_bf16, M * N)) return CONVROT_ERR_NULL;
+    if (!aligned(X_bf16, 16) || !aligned(Wq, 256) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) || !aligned(bias_bf16, 2))
+        return CONVROT_ERR_ALIGN;
+    return CONVROT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -61,6 +108,12 @@ const char *convrot_status_string(int status)
 }
 
 int convrot_version(void) { return CONVROT_VERSION; }
+
+int convrot_init(void)
+{
+    uint8_t *p = nullptr;
+    return scratch_of_current_device(&p);
+}
 
 int convrot_gemm_tile_rows(int64_t M, int64_t N)
 {
@@ -130,19 +183,29 @@ int convlinear4bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
                            int64_t M, int64_t N, int64_t K, int group, void *Y_bf16, void *workspace,
                            size_t workspace_bytes, void *stream)
 {
-    if (int rc = check_group(group)) return rc;
-    if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
-    if (int rc = check_k(K)) return rc;
-    if (K % group != 0) return CONVROT_ERR_SHAPE;
-    if (missing(X_bf16, M) || missing(Wq, N) || missing(w_scale, N) || missing(Y_bf16, M * N) ||
-        missing(workspace, M))
-        return CONVROT_ERR_NULL;
-    if (!aligned(X_bf16, 16) || !aligned(Wq, 256) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
-        !aligned(bias_bf16, 2) || !aligned(workspace, 256))
-        return CONVROT_ERR_ALIGN;
+    if (int rc = check_forward(X_bf16, Wq, w_scale, bias_bf16, M, N, K, group, Y_bf16)) return rc;
+    if (missing(workspace, M)) return CONVROT_ERR_NULL;
+    if (!aligned(workspace, 256)) return CONVROT_ERR_ALIGN;
     if (workspace_bytes < convrot_workspace_bytes(M, K)) return CONVROT_ERR_WORKSPACE;
 
     uint8_t *xq = static_cast<uint8_t *>(workspace);
+    float *xs = reinterpret_cast<float *>(xq + convrot_packed_bytes(M, K));
+    hipStream_t s = (hipStream_t)stream;
+    if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, 4, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
+    return from_hip(convrot::launch_gemm_w4a4(xq, xs, Wq, w_scale, bias_bf16, M, N, K, Y_bf16, nullptr, s));
+}
+
+int convlinear4bit_forward_noalloc(const void *X_bf16, const void *Wq, const float *w_scale, const void *bias_bf16,
+                                   int64_t M, int64_t N, int64_t K, int group, void *Y_bf16, void *stream)
+{
+    if (int rc = check_forward(X_bf16, Wq, w_scale, bias_bf16, M, N, K, group, Y_bf16)) return rc;
+    if (convrot_workspace_bytes(M, K) > CONVROT_NOALLOC_WORKSPACE_BYTES) return CONVROT_ERR_WORKSPACE;
+    if (M == 0 || N == 0) return CONVROT_OK;
+    uint8_t *xq = nullptr;
+    if (int rc = scratch_of_current_device(&xq)) return rc;
+    // Nothing in the array has to start at zero: the rotate+quantise kernel writes every byte of the rows below M
+    // (K padding included) and all M scales before the GEMM reads them; what an earlier call left in the rows
+    // past M of the last 32-row block only ever meets accumulators that are not stored.
     float *xs = reinterpret_cast<float *>(xq + convrot_packed_bytes(M, K));
     hipStream_t s = (hipStream_t)stream;
     if (hipError_t e = convrot::launch_rotquant(X_bf16, M, K, group, 4, xq, xs, s); e != hipSuccess) return CONVROT_ERR_HIP;
@@ -206,16 +269,9 @@ int convlinear8bit_forward(const void *X_bf16, const void *Wq, const float *w_sc
                            int64_t M, int64_t N, int64_t K, int group, void *Y_bf16, void *workspace,
                            size_t workspace_bytes, void *stream)
 {
-    if (int rc = check_group(group)) return rc;
-    if (M < 0 || N < 0 || M > INT32_MAX || N > INT32_MAX) return CONVROT_ERR_SHAPE;
-    if (int rc = check_k(K)) return rc;
-    if (K % group != 0) return CONVROT_ERR_SHAPE;
-    if (missing(X_bf16, M) || missing(Wq, N) || missing(w_scale, N) || missing(Y_bf16, M * N) ||
-        missing(workspace, M))
-        return CONVROT_ERR_NULL;
-    if (!aligned(X_bf16, 16) || !aligned(Wq, 256) || !aligned(Y_bf16, 16) || !aligned(w_scale, 4) ||
-        !aligned(bias_bf16, 2) || !aligned(workspace, 256))
-        return CONVROT_ERR_ALIGN;
+    if (int rc = check_forward(X_bf16, Wq, w_scale, bias_bf16, M, N, K, group, Y_bf16)) return rc;
+    if (missing(workspace, M)) return CONVROT_ERR_NULL;
+    if (!aligned(workspace, 256)) return CONVROT_ERR_ALIGN;
     if (workspace_bytes < convrot_workspace_bytes8(M, K)) return CONVROT_ERR_WORKSPACE;
 
     uint8_t *xq = static_cast<uint8_t *>(workspace);

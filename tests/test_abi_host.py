@@ -28,7 +28,7 @@ def declared_symbols():
 def test_header_symbols_are_exported(lib):
     from paper_2512_03673_amd import binding
     names = declared_symbols()
-    assert len(names) == 19
+    assert len(names) == 21
     assert sorted(binding.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -36,7 +36,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_size_queries_and_strings(lib):
     from paper_2512_03673_amd import binding as b
-    assert b.version() == 401
+    assert b.version() == 500
     # 4-bit code matrices: 3 KB blocks of 32 rows x 128 codes (6 bits per code), rows and K padded up to whole blocks
     assert b.packed_bytes(4608, 3072) == 4608 * 3072 * 3 // 4
     assert b.packed_bytes(37, 96) == 2 * 1 * 3072 and b.packed_bytes(3, 32) == 3072
@@ -102,6 +102,14 @@ def test_argument_validation_without_a_device(lib):
     assert fw(A, A, A, A, 4, 4, 1024, 16, A, A + 16, 1 << 20, None) == -4
     assert fw(A, A, A, A + 1, 4, 4, 1024, 16, A, A, 1 << 20, None) == -4
     assert fw(A, A, A, None, 4, 4, 1024, 16, A, A, 100, None) == -5
+    # the variant with the static workspace: same checks, the size limit instead of the workspace check, all on the host
+    fn = lib.convlinear4bit_forward_noalloc
+    assert fn(None, A, A, None, 4, 4, 1024, 16, A, None) == -1
+    assert fn(A, A, A, None, 4, 4, 1024, 5, A, None) == -3
+    assert fn(A, A, A, A + 1, 4, 4, 1024, 16, A, None) == -4
+    assert fn(A, A, A, None, 4, 4, 1040, 16, A, None) == -2
+    assert fn(A, A, A, None, 16896, 4, 12288, 16, A, None) == -5      # 156 MB of codes: beyond the 64 MiB array
+    assert fn(A, A, A, None, 0, 4, 1024, 16, A, None) == 0
     # W8A8 variant: same validation
     f8, g8, fw8 = lib.convrot_rotquant_act8, lib.convrot_w8a8_gemm_dequant, lib.convlinear8bit_forward
     assert f8(A, 4, 48, 16, A, A, None) == -2            # K % 32 != 0
