@@ -30,9 +30,18 @@ I8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA, published (the figure th
 # HBM bytes per launch of the headline shape from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per
 # dispatch), each scaled by what the same counter reads for a plain copy of known size (x2.0 and
 # x1.0); the runs are in profiles/gemm_w4a4_and_rotquant_headline_hbm_traffic_and_mfma_busy.md.
-# These are stored measurements of this build, not taken live (bench.py cannot run the profiler on itself).
+# These are stored measurements, not taken live (bench.py cannot run the profiler on itself): TRAFFIC_SOURCE
+# says which build of the kernels they were taken on.
 MEASURED_TRAFFIC_BYTES = {"gemm_w4a4_kernel": 83183 * 1024 * 2.0 + 110595 * 1024 * 1.0,
                           "rotquant_kernel": 14079 * 1024 * 2.0 + 10515 * 1024 * 1.0}
+TRAFFIC_SOURCE = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `python bench.py --calibrate-copy`, kernels as of commit "
+                  "67411f3 (library version 401); see profiles/")
+# What a register-only loop of the GEMM's MFMA sustains on this chip on operands with the workload's bit
+# statistics (8 wavefronts per compute unit, no memory traffic; 9.9 POP/s on all-zero operands): the chip lowers its
+# clock with operand activity, so this, not the nominal figure, is what a perfect kernel could reach on this data.
+MEASURED_FP6_MFMA_LOOP_TOPS = 6600.0
+MFMA_LOOP_SOURCE = "register-only v_mfma_f32_32x32x64_f8f6f4 loop on workload-like FP6 operands, MI355X of this pool"
+PREWARM_MS = 200.0           # load put on the device before anything is timed, whatever --warmup says
 COPY_BYTES = 512 << 20       # size of the calibration copy (--calibrate-copy)
 COLD_FOOTPRINT = 768 << 20   # kernel A, cold: bytes touched between two uses of one buffer set
 
@@ -115,7 +124,6 @@ def measure_layer(spec, cr, wl, torch, np, steps: int, warmup: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # the clocks of an idle MI355X take some 30 ms of load to settle: the default warm-up covers that
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -155,6 +163,14 @@ def main() -> int:
     def step():
         cr.convlinear4bit_forward(X, Wq, Ws, g, Y, ws)
 
+    # The clocks of an idle MI355X need tens of milliseconds of load to settle (the first hundred launches run
+    # a quarter slower): load the device for PREWARM_MS before the warm-up steps the caller asked for.
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < PREWARM_MS:
+        for _ in range(50):
+            step()
+        torch.cuda.synchronize()
+    prewarm_ms = (time.perf_counter() - t0) * 1e3
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -208,6 +224,7 @@ def main() -> int:
     tops_b = ops / (ms_b * 1e-3) / 1e12
     gbs_a = bytes_a / (ms_a * 1e-3) / 1e9
     gbs_a_cold = bytes_a / (ms_a_cold * 1e-3) / 1e9
+    bytes_a_nibble = 2.5 * M * K + 4.0 * M    # what the same pass would move with two codes per byte
     bytes_b_min = 0.75 * M * K + 0.75 * N * K + 4.0 * (M + N) + 2.0 * M * N
 
     out = {
@@ -218,11 +235,13 @@ def main() -> int:
         "config": {"workload": "cfg3_mlp/mlp_up: FLUX-style MLP up-projection", "M": M, "K": K, "N": N,
                    "group": g, "codes": "4-bit integers stored as FP6 E2M3, FP6 MFMA with exact fp32 accumulation, bf16 in/out",
                    "weights": "prepared offline (convrot_prepare_weight), not timed"},
-        "wall_ms_per_step": wall_ms,
+        "wall_ms_per_step": wall_ms, "prewarm_ms": prewarm_ms, "build": cr.build_info(),
         "kernels": {
             "rotquant_act": {"ms_cold": ms_a_cold, "GB/s_cold": gbs_a_cold, "frac_hbm_peak_cold": gbs_a_cold / HBM_PEAK_GBS,
-                             "ms_warm": ms_a, "GB/s_warm": gbs_a, "algorithmic_bytes": bytes_a,
-                             "traffic": MEASURED_TRAFFIC_BYTES["rotquant_kernel"],
+                             "ms_warm": ms_a, "GB/s_warm": gbs_a, "frac_hbm_peak_warm": gbs_a / HBM_PEAK_GBS,
+                             "algorithmic_bytes": bytes_a,
+                             "frac_hbm_peak_cold_at_2.5B_per_elem": bytes_a_nibble / (ms_a_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "traffic": MEASURED_TRAFFIC_BYTES["rotquant_kernel"], "traffic_source": TRAFFIC_SOURCE,
                              "note": f"cold: {nset} buffer sets in rotation ({COLD_FOOTPRINT >> 20} MiB between reuses); "
                                      "warm: one set, its 35 MB fit the 256 MB Infinity Cache"},
             "w4a4_gemm_dequant": {"ms": ms_b, "TOPS": tops_b, "frac_fp6_mfma_peak": tops_b / FP6_MFMA_PEAK_TOPS,
@@ -231,12 +250,14 @@ def main() -> int:
         },
         "roofline": {"kernel": "gemm_w4a4_kernel", "bound": "mfma", "achieved": tops_b, "peak": FP6_MFMA_PEAK_TOPS,
                      "unit": "TOP/s", "frac": tops_b / FP6_MFMA_PEAK_TOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES["gemm_w4a4_kernel"]},
+                     "traffic": MEASURED_TRAFFIC_BYTES["gemm_w4a4_kernel"], "traffic_source": TRAFFIC_SOURCE,
+                     "frac_vs_measured_peak": tops_b / MEASURED_FP6_MFMA_LOOP_TOPS,
+                     "measured_peak": MEASURED_FP6_MFMA_LOOP_TOPS, "measured_peak_source": MFMA_LOOP_SOURCE},
     }
     if args.all_configs:
         del X, Wq, Ws, Y, ws, Xq, Xs
         out["configs"] = [dict(config=name, **measure_layer(sp, cr, wl, torch, np, min(args.steps, 100), min(args.warmup, 100)))
-                          for name, layers in wl.CONFIGS.items() for sp in layers]
+                          for name, layers in list(wl.CONFIGS.items()) + list(wl.NEXT_CONFIGS.items()) for sp in layers]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(spec, x_bits, w_bits)
     print(json.dumps(out))

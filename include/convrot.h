@@ -92,6 +92,10 @@ const char *convrot_status_string(int status);
 /* Host.  CONVROT_VERSION of the loaded library. */
 int convrot_version(void);
 
+/* Host.  Static string naming the compiler the library was built with (the kernels rely on details of its code
+ * generation, so measurements should carry it), e.g. "clang 22.0.0git (...), HIP 7.2.26015". */
+const char *convrot_build_info(void);
+
 /*
  * Host.  Set-up of convlinear4bit_forward_noalloc for the calling thread's current device: looks up the
  * device address of that call's static workspace (which loads the library's device code onto the device if

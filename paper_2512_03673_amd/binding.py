@@ -25,7 +25,7 @@ EXPORTS = ("convrot_status_string", "convrot_version", "convrot_packed_bytes", "
            "convrot_prepare_weight8", "convrot_rotquant_act8", "convrot_w8a8_gemm_dequant",
            "convlinear8bit_forward", "convrot_w8a8_gemm_i32", "convrot_rotated_absmax",
            "convrot_workspace_bytes8", "convrot_packed_bytes8", "convrot_unpack_codes",
-           "convrot_gemm_tile_rows", "convrot_init", "convlinear4bit_forward_noalloc")
+           "convrot_gemm_tile_rows", "convrot_init", "convlinear4bit_forward_noalloc", "convrot_build_info")
 NOALLOC_WORKSPACE_BYTES = 64 << 20
 
 _lib = None
@@ -75,6 +75,8 @@ def load() -> ctypes.CDLL:
     lib.convrot_packed_bytes8.restype = sz
     lib.convrot_unpack_codes.argtypes = [vp, i64, i64, vp, vp]
     lib.convrot_unpack_codes.restype = i32
+    lib.convrot_build_info.argtypes = []
+    lib.convrot_build_info.restype = ctypes.c_char_p
     lib.convrot_init.argtypes = []
     lib.convrot_init.restype = i32
     lib.convlinear4bit_forward_noalloc.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]
@@ -91,6 +93,10 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return int(load().convrot_version())
+
+
+def build_info() -> str:
+    return load().convrot_build_info().decode()
 
 
 def init() -> None:

@@ -22,6 +22,8 @@ FLAGS = [
 
 def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
     """Compile every HIP source (always recompiles) and link the shared library."""
+    if verbose:   # the kernels lean on this compiler's code generation: show which one built them
+        print(subprocess.run(["hipcc", "--version"], capture_output=True, text=True).stdout.strip(), flush=True)
     objdir = os.path.join(HERE, "_build", os.path.basename(out).replace(".so", ""))
     os.makedirs(objdir, exist_ok=True)
 

@@ -109,6 +109,13 @@ const char *convrot_status_string(int status)
 
 int convrot_version(void) { return CONVROT_VERSION; }
 
+#define CONVROT_STR2(x) #x
+#define CONVROT_STR(x) CONVROT_STR2(x)
+const char *convrot_build_info(void)
+{
+    return "clang " __clang_version__ ", HIP " CONVROT_STR(HIP_VERSION_MAJOR) "." CONVROT_STR(HIP_VERSION_MINOR) "." CONVROT_STR(HIP_VERSION_PATCH);
+}
+
 int convrot_init(void)
 {
     uint8_t *p = nullptr;

@@ -28,7 +28,7 @@ def declared_symbols():
 def test_header_symbols_are_exported(lib):
     from paper_2512_03673_amd import binding
     names = declared_symbols()
-    assert len(names) == 21
+    assert len(names) == 22
     assert sorted(binding.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -51,6 +51,7 @@ def test_size_queries_and_strings(lib):
     assert b.workspace_bytes(0, 32) == 0
     assert b.workspace_bytes8(4608, 3072) == 4608 * 3072 + 4608 * 4
     assert b.workspace_bytes8(3, 32) == 1024 + 256
+    assert "clang" in b.build_info() and "HIP" in b.build_info()
     assert b.status_string(0) == "ok"
     assert "group" in b.status_string(-3)
     assert b.status_string(-99) == "unknown status"
