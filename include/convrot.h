@@ -62,6 +62,11 @@
  *
  * Quantiser (both operands): a = max_k |x'[k]| over the rotated row, s = a / 7 in fp32 (s = 1
  * when a == 0), q = clamp(round_half_even(x' / s), -7, 7).
+ *
+ * Values.  X and W must be finite.  A NaN or an infinity leaves the scale and the codes of its own
+ * row undefined (as any absmax quantiser does) and, because 64 units of 16 elements are rotated in
+ * one matrix instruction, may do the same to the other rows of the same block of 32 rows (16 in the
+ * 8-bit variant); rows of other blocks are not affected.
  */
 #ifndef CONVROT_H
 #define CONVROT_H

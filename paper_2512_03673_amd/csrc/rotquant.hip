@@ -4,14 +4,17 @@
 //
 // Work split.  A "unit" is 16 consecutive elements of a row (32 B of bf16 in, 12 B of codes out)
 // and belongs to one lane.  A row is spread over T = 64*Wv lanes (Wv wavefronts); lane t of the
-// row owns units t, t+T, t+2T, ... (U of them), so one wavefront load instruction covers a
-// contiguous 2 KB span of the row.  The whole row stays in registers between the absmax
+// row owns units t, t+T, t+2T, ... (U of them), so the two load instructions of a wavefront for one
+// such set of units cover a contiguous 2 KB span of the row.  The whole row stays in registers between the absmax
 // reduction and the rounding, so X is read from HBM exactly once.
 //
 // Rotation.  H_g = H_4 (x) ... (x) H_4 (Thm 3.3) is separable: one radix-4 step per base-4 digit
 // of the in-group index.  With the printed H_4 (all ones, -1 on the anti-diagonal) a step is
 //     y_j = (x_0 + x_1 + x_2 + x_3) - 2 x_{3-j}.
-// Digits 0 and 1 live inside a lane's 16 elements, so the index flip 3-j is register renaming.
+// Digits 0 and 1 live inside a lane's 16 elements: a 16 x 16 matrix of +-1 (H_4 (x) H_4) applied to
+// every unit, which is what the otherwise idle matrix pipe does for 64 units at a time, the bf16 -> fp32
+// widening and the hand-over of each unit to its lane included (rotation_operand below): the vector ALU,
+// which bounds this kernel on small inputs, sees none of it.
 // Digits 2, 3 (g = 64, 256) run across lanes with DPP adds and digit 4 (g = 1024) with
 // wavefront shuffles; there the step is taken as y_j = s - 2 x_j (the matrix J - 2I, which is
 // the printed matrix with its columns reversed) and the flip is applied once, for free, to the
@@ -41,6 +44,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int v6u __attribute__((ext_vector_type(6)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x)
@@ -64,26 +68,10 @@ __device__ __forceinline__ float radix4_lanes_shfl(float x, int m1, int m2)
     return fmaf(-2.0f, x, s);
 }
 
-// Printed H_4 on four registers: y_j = s - 2 x_{3-j}.
-__device__ __forceinline__ void radix4_regs(float &a, float &b, float &c, float &d)
-{
-    float s = (a + b) + (c + d);
-    float na = fmaf(-2.0f, d, s);
-    float nb = fmaf(-2.0f, c, s);
-    float nc = fmaf(-2.0f, b, s);
-    float nd = fmaf(-2.0f, a, s);
-    a = na; b = nb; c = nc; d = nd;
-}
-
+// The digits that live across lanes (in-group index digits 2 and up), on a unit whose digits 0 and 1 are done.
 template <int G>
-__device__ __forceinline__ void rotate_unit(float (&v)[kUnit])
+__device__ __forceinline__ void rotate_lanes(float (&v)[kUnit])
 {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) radix4_regs(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-    if constexpr (G >= 16) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) radix4_regs(v[e], v[e + 4], v[e + 8], v[e + 12]);
-    }
     if constexpr (G >= 64) {  // lanes l ^ 1, l ^ 2: quad_perm [1,0,3,2] then [2,3,0,1]
 #pragma unroll
         for (int e = 0; e < kUnit; ++e) v[e] = radix4_lanes_dpp<0xB1, 0x4E>(v[e]);
@@ -96,6 +84,45 @@ __device__ __forceinline__ void rotate_unit(float (&v)[kUnit])
 #pragma unroll
         for (int e = 0; e < kUnit; ++e) v[e] = radix4_lanes_shfl(v[e], 16, 32);
     }
+}
+
+// The digits inside a unit on the matrix pipe.  v_mfma_f32_32x32x16_bf16 computes D = A B with B a 16 x 32
+// matrix of bf16 whose column n is spread over lanes n (rows 0-7) and n + 32 (rows 8-15), eight consecutive
+// rows = 16 contiguous bytes each, and leaves column n of D in lanes n (rows 8 b + r) and n + 32 (rows
+// 8 b + 4 + r), register 4 b + r.  With the 32 units of lanes 0-31 as the columns of B and the 16 rows of
+// R = H_4 (x) H_4 (I_4 (x) H_4 for g = 4; both symmetric) put at the rows 8 b + r of A, zeros elsewhere, lane n
+// receives its whole rotated unit in element order, as fp32; a second MFMA with the rows of R at 8 b + 4 + r and
+// the units of lanes 32-63 as B accumulates the other half of the wavefront on top.  Products with +-1 are
+// exact and the sums are taken in fp32, as the register butterflies take them; the bf16 -> fp32 widening
+// comes with it.  The price is that a lane fetches halves of two other lanes' units instead of its own.
+// Returns this lane's eight entries of A for the MFMA that serves lanes 32 * half ... 32 * half + 31.
+template <int G>
+__device__ __forceinline__ v8bf rotation_operand(int lane, int half)
+{
+    const int i = lane & 31, kb = lane >> 5;
+    const int o = 4 * (i >> 3) + (i & 3);             // element of the unit that accumulator row i holds
+    const bool mine = ((i >> 2) & 1) == half;
+    union { v8bf v; uint16_t u[8]; } a;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+        const int k = 8 * kb + x;
+        const bool neg = ((o & 3) + (k & 3) == 3) != (G >= 16 && (o >> 2) + (k >> 2) == 3);
+        const bool zero = !mine || (G < 16 && (o >> 2) != (k >> 2));
+        a.u[x] = zero ? (uint16_t)0 : (neg ? (uint16_t)0xBF80 : (uint16_t)0x3F80);    // bf16 0, -1, +1
+    }
+    return a.v;
+}
+
+// Digits 0 and 1 of 64 units, one per lane: b0 / b1 = bytes 16 (lane / 32) ... + 15 of the units owned by lanes
+// lane % 32 and lane % 32 + 32; v = this lane's unit.
+__device__ __forceinline__ void rotate_units_mfma(const v8bf &rot0, const v8bf &rot1, const u32x4 &b0, const u32x4 &b1,
+                                                  float (&v)[kUnit])
+{
+    v16f d = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rot0, __builtin_bit_cast(v8bf, b0), d, 0, 0, 0);
+    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rot1, __builtin_bit_cast(v8bf, b1), d, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < kUnit; ++e) v[e] = d[e];
 }
 
 template <int G>
@@ -115,8 +142,10 @@ constexpr float group_norm() { return G == 4 ? 0.5f : G == 16 ? 0.25f : G == 64 
 // grid.x = 8 * ceil(rows / (8 * group rows)) * group rows / rows per block (see the row mapping below).
 // BITS = 4: codes in [-7, 7], stored as FP6 E2M3 (e2m3_layout.h); BITS = 8 (the W8A8 variant of the layer): one
 // int8 per code, [-127, 127] (panel_layout.h).
+// (At least two wavefronts per SIMD, i.e. at most 256 registers per lane: then the compiler keeps the MFMA results in
+// ordinary registers instead of copying them out of the accumulation registers, one move per element.)
 template <int G, int U, int BLOCK, int BITS, int RPW>
-__global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
+__global__ __launch_bounds__(BLOCK, BLOCK <= 256 ? 2 : 1) void rotquant_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
                                                          int T, uint8_t *__restrict__ Xq,
                                                          float *__restrict__ scale)
 {
@@ -137,32 +166,39 @@ __global__ __launch_bounds__(BLOCK) void rotquant_kernel(const uint16_t *__restr
     const bool row_ok = row < rows;
     const int units = K / kUnit;
 
-    // All loads are issued up front and unconditionally: a lane whose unit (or row) does not exist
-    // fetches the last unit of the last row instead and is masked out of the absmax and the stores.
+    // All loads are issued up front and unconditionally: a unit (or row) that does not exist is replaced
+    // by the last unit of the last row, and its owner is masked out of the absmax and the stores.
     // K % g == 0 makes a rotation group all-valid or all-invalid, so such lanes never feed valid ones.
-    const int64_t row_c = row_ok ? row : rows - 1;
-    const uint16_t *xrow = X + row_c * (int64_t)K;
+    // The units are fetched as operands of the rotation MFMAs (rotation_operand): for h = 0, 1 this lane
+    // loads bytes 16 kb ... 16 kb + 15 (kb = lane / 32) of the units owned by lane (lane % 32) + 32 h.
+    const int lane = tid & 63;
+    const uint16_t *src[2];
+    int t_src[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int otid = (tid & ~63) | (lane & 31) | (h << 5);                     // the owner
+        const int orib = RPW == 1 ? rib : (otid & 63) >> 4;                        // (a wavefront lies inside one row if RPW == 1)
+        t_src[h] = RPW == 1 ? otid - rib * T : (otid >> 6) * 16 + (otid & 15);
+        const int64_t orow = row - rib + orib;
+        src[h] = X + (orow < rows ? orow : rows - 1) * (int64_t)K + 8 * (lane >> 5);
+    }
     u32x4 raw[U][2];
 #pragma unroll
     for (int i = 0; i < U; ++i) {
-        const int unit = min(i * T + t, units - 1);
-        const u32x4 *p = reinterpret_cast<const u32x4 *>(xrow + (int64_t)unit * kUnit);
-        raw[i][0] = __builtin_nontemporal_load(p);
-        raw[i][1] = __builtin_nontemporal_load(p + 1);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int unit = min(i * T + t_src[h], units - 1);
+            raw[i][h] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src[h] + (int64_t)unit * kUnit));
+        }
     }
+    const v8bf rot0 = rotation_operand<G>(lane, 0), rot1 = rotation_operand<G>(lane, 1);
 
     float v[U][kUnit];
     float amax = 0.0f;
 #pragma unroll
     for (int i = 0; i < U; ++i) {
-        const uint32_t w[8] = {raw[i][0].x, raw[i][0].y, raw[i][0].z, raw[i][0].w,
-                               raw[i][1].x, raw[i][1].y, raw[i][1].z, raw[i][1].w};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            v[i][2 * j] = __uint_as_float(w[j] << 16);
-            v[i][2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
-        }
-        rotate_unit<G>(v[i]);
+        rotate_units_mfma(rot0, rot1, raw[i][0], raw[i][1], v[i]);
+        rotate_lanes<G>(v[i]);
         float m = 0.0f;
 #pragma unroll
         for (int e = 0; e < kUnit; ++e) m = fmaxf(m, fabsf(v[i][e]));
@@ -378,7 +414,7 @@ __device__ __forceinline__ void sylvester_unit(float (&v)[kUnit], int lane)
 // the rotated activations for KIND 0 = no rotation, 1 = the layer's regular Hadamard rotation, 2 = the
 // Sylvester Hadamard matrix of the same order.  One wavefront per row, 1024 elements per pass.
 template <int G, int KIND>
-__global__ __launch_bounds__(256) void rotated_absmax_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
+__global__ __launch_bounds__(256, 2) void rotated_absmax_kernel(const uint16_t *__restrict__ X, int64_t rows, int K,
                                                              float *__restrict__ out)
 {
     const int lane = threadIdx.x & 63;
@@ -387,19 +423,30 @@ __global__ __launch_bounds__(256) void rotated_absmax_kernel(const uint16_t *__r
     const int units = K / kUnit;
     const uint16_t *xrow = X + row * (int64_t)K;
     float amax = 0.0f;
+    v8bf rot0, rot1;
+    if constexpr (KIND == 1) { rot0 = rotation_operand<G>(lane, 0); rot1 = rotation_operand<G>(lane, 1); }
     for (int base = 0; base < units; base += 64) {
         const int unit = base + lane;
         const bool ok = unit < units;            // K % g == 0: a rotation group is all-valid or all-invalid
-        const u32x4 *p = reinterpret_cast<const u32x4 *>(xrow + (int64_t)(ok ? unit : units - 1) * kUnit);
-        const u32x4 lo = p[0], hi = p[1];
-        const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         float v[kUnit];
+        if constexpr (KIND == 1) {
+            // the layer's rotation, with the arithmetic of the rotate+quantise kernel (bit-identical maxima)
+            const int u0 = min(base + (lane & 31), units - 1), u1 = min(base + (lane & 31) + 32, units - 1);
+            const uint16_t *half = xrow + 8 * (lane >> 5);
+            const u32x4 b0 = *reinterpret_cast<const u32x4 *>(half + (int64_t)u0 * kUnit);
+            const u32x4 b1 = *reinterpret_cast<const u32x4 *>(half + (int64_t)u1 * kUnit);
+            rotate_units_mfma(rot0, rot1, b0, b1, v);
+            rotate_lanes<G>(v);
+        } else {
+            const u32x4 *p = reinterpret_cast<const u32x4 *>(xrow + (int64_t)(ok ? unit : units - 1) * kUnit);
+            const u32x4 lo = p[0], hi = p[1];
+            const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            v[2 * j] = __uint_as_float(w[j] << 16);
-            v[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+            for (int j = 0; j < 8; ++j) {
+                v[2 * j] = __uint_as_float(w[j] << 16);
+                v[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+            }
         }
-        if constexpr (KIND == 1) rotate_unit<G>(v);
         if constexpr (KIND == 2) sylvester_unit<G>(v, lane);
         float m = 0.0f;
 #pragma unroll
