@@ -295,27 +295,31 @@ __global__ __launch_bounds__(BLOCK, BLOCK <= 256 ? 2 : 1) void rotquant_kernel(c
             // the two brackets agree on every code exactly when the sum of |difference of their bit patterns|
             // is zero (the patterns share their upper halves, so the 16-bit SAD sees the whole difference)
             uint32_t disagree = 0;
-            v16f qa, qb;    // conversion sources
+            v16f qa, qb;    // conversion sources; the halves of a missing second unit stay unset (their output is not used)
 #pragma unroll
             for (int e = 0; e < kUnit; ++e) {
                 const float lo0 = fmaf(v[i][e], r_lo, kMagic), hi0 = fmaf(v[i][e], r_hi, kMagic);
                 disagree = __builtin_amdgcn_sad_u16(__float_as_uint(lo0), __float_as_uint(hi0), disagree);
-                float q1 = 0.0f;
+                if (e < 8) qa[e] = lo0 - kMagic;
+                else qb[e - 8] = lo0 - kMagic;
                 if (pair) {
                     const float lo1 = fmaf(v[i1][e], r_lo, kMagic), hi1 = fmaf(v[i1][e], r_hi, kMagic);
                     disagree = __builtin_amdgcn_sad_u16(__float_as_uint(lo1), __float_as_uint(hi1), disagree);
-                    q1 = lo1 - kMagic;
+                    if (e < 8) qa[8 + e] = lo1 - kMagic;
+                    else qb[e] = lo1 - kMagic;
                 }
-                if (e < 8) { qa[e] = lo0 - kMagic; qa[8 + e] = q1; }
-                else { qb[e - 8] = lo0 - kMagic; qb[e] = q1; }
             }
             if (__builtin_amdgcn_ballot_w64(disagree != 0) != 0) {   // wavefront-uniform, rare
 #pragma unroll
                 for (int e = 0; e < kUnit; ++e) {
                     const float q0 = exact_code(v[i][e]);
-                    const float q1 = pair ? exact_code(v[i1][e]) : 0.0f;
-                    if (e < 8) { qa[e] = q0; qa[8 + e] = q1; }
-                    else { qb[e - 8] = q0; qb[e] = q1; }
+                    if (e < 8) qa[e] = q0;
+                    else qb[e - 8] = q0;
+                    if (pair) {
+                        const float q1 = exact_code(v[i1][e]);
+                        if (e < 8) qa[8 + e] = q1;
+                        else qb[e] = q1;
+                    }
                 }
             }
             const v6u packed = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qa, qb, 1.0f);
