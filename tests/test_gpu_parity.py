@@ -61,6 +61,22 @@ def test_rotquant_small_k_multiples_of_32(cr, g):
 
 
 @pytest.mark.parametrize("g", GROUPS)
+@pytest.mark.parametrize("M,K", [(64, 3072), (7, 12288)])
+def test_rotquant_with_a_wide_spread_of_exponents(cr, g, M, K):
+    # magnitudes from 2^-12 to 2^12 inside every unit of 16 elements: the sums of a rotation group are then not
+    # exactly representable in fp32, so the order and width of the accumulation (registers, matrix pipe) show
+    # as roundings of the rotated values; the codes must stay inside the gate against the fp64 oracle
+    if K % g:
+        pytest.skip("K not a multiple of g")
+    rng = np.random.default_rng(1000 + g + M)
+    x = rng.standard_normal((M, K)) * np.exp2(rng.integers(-12, 13, size=(M, K)).astype(np.float64))
+    bits = wl.f32_to_bf16_bits(x.astype(np.float32))
+    q, s = gpu_rotquant(cr, bits, g)
+    qo, so = oracle.rotquant(bits, g)
+    check_codes(q, s, qo, so, f"wide exponents g={g} M={M} K={K}")
+
+
+@pytest.mark.parametrize("g", GROUPS)
 def test_rotquant_closed_forms_on_gpu(cr, g):
     # the same special cases that pin the oracle, now on the HIP path: exact equality expected
     K = 4 * g if g >= 16 else 64
