@@ -281,12 +281,19 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
 #pragma unroll
         for (int i = 0; i < XF; ++i) sxm[i] = sx_lds[wm0 + i * 32 + (lane & 31)];
         uint8_t *stage = lds + wave * (32 * kEpiPitch);          // this wavefront's 32 x WN bf16 staging tile
-        // read-back: a row of WN bf16 is WN / 8 pieces of 16 bytes; 8 lanes per row (8 rows per pass) when
-        // that is 8, else 16 lanes per row, WN / 8 of them active (4 rows per pass)
-        constexpr int kRbLanes = WN / 8 <= 8 ? 8 : 16, kRbRows = 64 / kRbLanes;
-        const int rb_row = lane / kRbLanes, rb_piece = lane % kRbLanes;
-        const bool rb_active = rb_piece < WN / 8;
-        const int ncol = n0 + wn0 + rb_piece * 8;               // first of this lane's 8 output columns
+        // read-back: the 32 rows of WN bf16 are 32 * WN / 8 pieces of 16 bytes, dealt to the 64 lanes in order
+        // (piece p = 64 pass + lane: row p / (WN / 8), columns 8 (p % (WN / 8)) ...), so every pass has all
+        // lanes at work and stores whole rows of the wavefront tile back to back
+        constexpr int kRowPieces = WN / 8, kRbPasses = 32 * kRowPieces / 64;
+        static_assert(kRbPasses * 64 == 32 * kRowPieces, "read-back passes");
+        const int rb_row0 = lane / kRowPieces, rb_piece0 = lane % kRowPieces;   // pass 0; 64 more pieces per pass
+        // the column scales of the lane's accumulator registers, fetched once for all XF row blocks
+        float4 swv[WF][4];
+#pragma unroll
+        for (int j = 0; j < WF; ++j)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+                swv[j][rb] = *reinterpret_cast<const float4 *>(sw_lds + wn0 + j * 32 + rb * 8 + (lane >> 5) * 4);
         auto body = [&](auto INTERIOR, auto BIAS) {
 #pragma unroll
             for (int i = 0; i < XF; ++i) {
@@ -296,7 +303,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
 #pragma unroll
                     for (int rb = 0; rb < 4; ++rb) {
                         const int col = j * 32 + rb * 8 + (lane >> 5) * 4;
-                        const float4 sw = *reinterpret_cast<const float4 *>(sw_lds + wn0 + col);
+                        const float4 sw = swv[j][rb];
                         float y[4] = {(acc[i][j][rb * 4 + 0] * sxm[i]) * sw.x, (acc[i][j][rb * 4 + 1] * sxm[i]) * sw.y,
                                       (acc[i][j][rb * 4 + 2] * sxm[i]) * sw.z, (acc[i][j][rb * 4 + 3] * sxm[i]) * sw.w};
                         if constexpr (decltype(BIAS)::value) {
@@ -308,11 +315,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_w4a4_kernel(
                     }
                 // the same wavefront reads back row-contiguous
 #pragma unroll
-                for (int it = 0; it < 32 / kRbRows; ++it) {
-                    const int r = it * kRbRows + rb_row;
-                    if (!rb_active) continue;
-                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + rb_piece * 16);
-                    const int mo = mrow + r;
+                for (int it = 0; it < kRbPasses; ++it) {
+                    int piece = rb_piece0 + (it * 64) % kRowPieces, r = rb_row0 + (it * 64) / kRowPieces;
+                    if ((it * 64) % kRowPieces != 0 && piece >= kRowPieces) { piece -= kRowPieces; ++r; }
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stage + r * kEpiPitch + piece * 16);
+                    const int mo = mrow + r, ncol = n0 + wn0 + piece * 8;
                     uint16_t *dst = Y + (int64_t)mo * N + ncol;
                     if constexpr (decltype(INTERIOR)::value) {
                         *reinterpret_cast<uint4 *>(dst) = v;
