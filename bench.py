@@ -32,10 +32,10 @@ I8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA, published (the figure th
 # x1.0); the runs are in profiles/gemm_w4a4_and_rotquant_headline_hbm_traffic_and_mfma_busy.md.
 # These are stored measurements, not taken live (bench.py cannot run the profiler on itself): TRAFFIC_SOURCE
 # says which build of the kernels they were taken on.
-MEASURED_TRAFFIC_BYTES = {"gemm_w4a4_kernel": 83183 * 1024 * 2.0 + 110593 * 1024 * 1.0,
+MEASURED_TRAFFIC_BYTES = {"gemm_w4a4_kernel": 83177 * 1024 * 2.0 + 110613 * 1024 * 1.0,
                           "rotquant_kernel": 13883 * 1024 * 2.0 + 10386 * 1024 * 1.0}
 TRAFFIC_SOURCE = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `python bench.py --calibrate-copy`, library version 500 "
-                  "(kernel sources as of commit a29a974); see profiles/")
+                  "(kernel sources as of commit 1f837fa); see profiles/")
 # What a register-only loop of the GEMM's MFMA sustains on this chip on operands with the workload's bit
 # statistics (8 wavefronts per compute unit, no memory traffic; 9.9 POP/s on all-zero operands): the chip lowers its
 # clock with operand activity, so this, not the nominal figure, is what a perfect kernel could reach on this data.
