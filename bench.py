@@ -86,21 +86,27 @@ def cpu_baseline(spec, x_bits, w_bits, budget_s: float = 15.0):
             "ms_per_step": dt / rows * spec.M * 1e3}
 
 
-def measure_layer(spec, cr, wl, torch, np, steps: int, warmup: int):
-    """Kernel A, kernel B, the fused forward and the offline weight preparation of one layer (ms, rates)."""
+def measure_layer(spec, cr, wl, torch, np, steps: int, warmup: int, bits: int = 4):
+    """Kernel A, kernel B, the fused forward and the offline weight preparation of one layer (ms, rates); bits = 8:
+    the W8A8 variant of the layer (int8 codes, int8 MFMA)."""
     stream = torch.cuda.current_stream()
     M, K, N, g = spec.M, spec.K, spec.N, spec.group
+    prepare, rotquant, gemm, forward, wsbytes = (
+        (cr.convrot_prepare_weight, cr.convrot_rotquant_act, cr.convrot_w4a4_gemm_dequant, cr.convlinear4bit_forward,
+         cr.workspace_bytes) if bits == 4 else
+        (cr.convrot_prepare_weight8, cr.convrot_rotquant_act8, cr.convrot_w8a8_gemm_dequant, cr.convlinear8bit_forward,
+         cr.workspace_bytes8))
     x_bits, w_bits = wl.make_layer(spec)
     X = torch.from_numpy(x_bits.view(np.int16)).cuda().view(torch.bfloat16)
     W = torch.from_numpy(w_bits.view(np.int16)).cuda().view(torch.bfloat16)
-    Wq, Ws = cr.convrot_prepare_weight(W, g)
-    Xq, Xs = cr.convrot_rotquant_act(X, g)
+    Wq, Ws = prepare(W, g)
+    Xq, Xs = rotquant(X, g)
     Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-    ws = torch.empty((cr.workspace_bytes(M, K),), dtype=torch.uint8, device="cuda")
-    fns = {"forward": lambda: cr.convlinear4bit_forward(X, Wq, Ws, g, Y, ws),
-           "gemm": lambda: cr.convrot_w4a4_gemm_dequant(Xq, Xs, Wq, Ws, K, Y),
-           "rotquant": lambda: cr.convrot_rotquant_act(X, g, Xq, Xs),
-           "prepare_weight": lambda: cr.convrot_prepare_weight(W, g, Wq, Ws)}
+    ws = torch.empty((wsbytes(M, K),), dtype=torch.uint8, device="cuda")
+    fns = {"forward": lambda: forward(X, Wq, Ws, g, Y, ws),
+           "gemm": lambda: gemm(Xq, Xs, Wq, Ws, K, Y),
+           "rotquant": lambda: rotquant(X, g, Xq, Xs),
+           "prepare_weight": lambda: prepare(W, g, Wq, Ws)}
     for _ in range(warmup):
         fns["forward"]()
     ms = {}
@@ -110,15 +116,20 @@ def measure_layer(spec, cr, wl, torch, np, steps: int, warmup: int):
         torch.cuda.synchronize()
         ms[name] = time_region(fn, steps, torch, stream)
     torch.cuda.synchronize()
-    ops, bytes_a, bytes_w = 2.0 * M * K * N, 2.75 * M * K + 4.0 * M, 2.75 * N * K + 4.0 * N
-    return {"layer": spec.name, "M": M, "K": K, "N": N, "group": g,
-            "forward_ms": ms["forward"], "forward_TOPS": ops / ms["forward"] / 1e9,
-            "gemm_ms": ms["gemm"], "gemm_TOPS": ops / ms["gemm"] / 1e9,
-            "gemm_frac_fp6_mfma_peak": ops / ms["gemm"] / 1e9 / FP6_MFMA_PEAK_TOPS,
-            "gemm_vs_i8_mfma_peak": ops / ms["gemm"] / 1e9 / I8_MFMA_PEAK_TOPS,
-            "rotquant_ms_warm": ms["rotquant"], "rotquant_GB/s_warm": bytes_a / ms["rotquant"] / 1e6,
-            "rotquant_frac_hbm_peak_warm": bytes_a / ms["rotquant"] / 1e6 / HBM_PEAK_GBS,
-            "prepare_weight_ms": ms["prepare_weight"], "prepare_weight_GB/s": bytes_w / ms["prepare_weight"] / 1e6}
+    code_bytes = 0.75 if bits == 4 else 1.0
+    ops, bytes_a, bytes_w = 2.0 * M * K * N, (2.0 + code_bytes) * M * K + 4.0 * M, (2.0 + code_bytes) * N * K + 4.0 * N
+    out = {"layer": spec.name, "M": M, "K": K, "N": N, "group": g,
+           "forward_ms": ms["forward"], "forward_TOPS": ops / ms["forward"] / 1e9,
+           "gemm_ms": ms["gemm"], "gemm_TOPS": ops / ms["gemm"] / 1e9}
+    if bits == 4:
+        out["gemm_frac_fp6_mfma_peak"] = ops / ms["gemm"] / 1e9 / FP6_MFMA_PEAK_TOPS
+        out["gemm_vs_i8_mfma_peak"] = ops / ms["gemm"] / 1e9 / I8_MFMA_PEAK_TOPS
+    else:
+        out["gemm_frac_i8_mfma_peak"] = ops / ms["gemm"] / 1e9 / I8_MFMA_PEAK_TOPS
+    out.update({"rotquant_ms_warm": ms["rotquant"], "rotquant_GB/s_warm": bytes_a / ms["rotquant"] / 1e6,
+                "rotquant_frac_hbm_peak_warm": bytes_a / ms["rotquant"] / 1e6 / HBM_PEAK_GBS,
+                "prepare_weight_ms": ms["prepare_weight"], "prepare_weight_GB/s": bytes_w / ms["prepare_weight"] / 1e6})
+    return out
 
 
 def main() -> int:
@@ -129,7 +140,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true")
     ap.add_argument("--all-configs", action="store_true",
-                    help="also time every layer of the five benchmark configurations (adds a 'configs' list)")
+                    help="also time every layer of the five benchmark configurations and the next-row layers (adds a "
+                         "'configs' list) and the W8A8 variant on four of them ('configs_w8a8')")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards over tokens without any "
@@ -258,6 +270,11 @@ def main() -> int:
         del X, Wq, Ws, Y, ws, Xq, Xs
         out["configs"] = [dict(config=name, **measure_layer(sp, cr, wl, torch, np, min(args.steps, 100), min(args.warmup, 100)))
                           for name, layers in list(wl.CONFIGS.items()) + list(wl.NEXT_CONFIGS.items()) for sp in layers]
+        # the W8A8 variant of the layer (int8 codes on the int8 MFMA) on the large FLUX shapes
+        w8 = [sp for name, layers in list(wl.CONFIGS.items()) + list(wl.NEXT_CONFIGS.items()) for sp in layers
+              if sp.name in ("mlp_up", "mlp_down", "hires_down", "fused_out")]
+        out["configs_w8a8"] = [measure_layer(sp, cr, wl, torch, np, min(args.steps, 100), min(args.warmup, 100), bits=8)
+                               for sp in w8]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(spec, x_bits, w_bits)
     print(json.dumps(out))
