@@ -96,3 +96,29 @@ def test_noalloc_in_a_hip_graph(cr):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(Y, y_eager), f"replay {rep}"
+
+
+def test_init_from_many_host_threads(cr):
+    # convrot_init is idempotent and may be raced: every thread gets CONVROT_OK and the array's address is taken once;
+    # the entry point works afterwards
+    import threading
+    results = []
+
+    def worker():
+        try:
+            cr.init()
+            results.append(0)
+        except Exception as e:          # noqa: BLE001 - reported through the assertion below
+            results.append(e)
+
+    threads = [threading.Thread(target=worker) for _ in range(16)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert results == [0] * 16, results
+    spec, x, w, X, wq, ws, bias = make(cr, 70, 256, 200, 16, 61, False)
+    Y = cr.convlinear4bit_forward_noalloc(X, wq, ws, 16, torch.empty((70, 200), dtype=torch.bfloat16, device="cuda"))
+    y_ref = cr.convlinear4bit_forward(X, wq, ws, 16)
+    torch.cuda.synchronize()
+    assert torch.equal(Y.view(torch.int16), y_ref.view(torch.int16))
