@@ -58,6 +58,22 @@ def time_region(fn, steps: int, torch, stream) -> float:
     return e0.elapsed_time(e1) / steps
 
 
+def time_region_chunks(fn, steps: int, torch, stream, chunks: int = 10):
+    """As time_region, with an event recorded after every steps / chunks calls as well (recording syncs nothing): returns
+    (ms per call over the whole region, median and minimum of the per-chunk ms per call)."""
+    chunks = max(1, min(chunks, steps))
+    bounds = [steps * c // chunks for c in range(chunks + 1)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(chunks + 1)]
+    ev[0].record(stream)
+    for c in range(chunks):
+        for _ in range(bounds[c + 1] - bounds[c]):
+            fn()
+        ev[c + 1].record(stream)
+    ev[-1].synchronize()
+    per = sorted(ev[c].elapsed_time(ev[c + 1]) / (bounds[c + 1] - bounds[c]) for c in range(chunks))
+    return ev[0].elapsed_time(ev[-1]) / steps, per[len(per) // 2], per[0]
+
+
 def cpu_baseline(spec, x_bits, w_bits, budget_s: float = 15.0):
     """The oracle, untuned, on the host cores: same forward (weights prepared untimed) on a row sample."""
     import numpy as np
@@ -187,7 +203,7 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ms_step = time_region(step, args.steps, torch, stream)
+    ms_step, ms_step_median, ms_step_min = time_region_chunks(step, args.steps, torch, stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -201,7 +217,7 @@ def main() -> int:
     for _ in range(max(5, args.warmup // 4)):
         kern_a(); kern_b()
     torch.cuda.synchronize()
-    ms_b = time_region(kern_b, args.steps, torch, stream)
+    ms_b, ms_b_median, ms_b_min = time_region_chunks(kern_b, args.steps, torch, stream)
     ms_a = time_region(kern_a, args.steps, torch, stream)
     torch.cuda.synchronize()
 
@@ -247,6 +263,7 @@ def main() -> int:
         "config": {"workload": "cfg3_mlp/mlp_up: FLUX-style MLP up-projection", "M": M, "K": K, "N": N,
                    "group": g, "codes": "4-bit integers stored as FP6 E2M3, FP6 MFMA with exact fp32 accumulation, bf16 in/out",
                    "weights": "prepared offline (convrot_prepare_weight), not timed"},
+        "ms_per_step_median_of_tenths": ms_step_median, "ms_per_step_min_of_tenths": ms_step_min,
         "wall_ms_per_step": wall_ms, "prewarm_ms": prewarm_ms, "build": cr.build_info(),
         "kernels": {
             "rotquant_act": {"ms_cold": ms_a_cold, "GB/s_cold": gbs_a_cold, "frac_hbm_peak_cold": gbs_a_cold / HBM_PEAK_GBS,
@@ -256,7 +273,7 @@ def main() -> int:
                              "traffic": MEASURED_TRAFFIC_BYTES["rotquant_kernel"], "traffic_source": TRAFFIC_SOURCE,
                              "note": f"cold: {nset} buffer sets in rotation ({COLD_FOOTPRINT >> 20} MiB between reuses); "
                                      "warm: one set, its 35 MB fit the 256 MB Infinity Cache"},
-            "w4a4_gemm_dequant": {"ms": ms_b, "TOPS": tops_b, "frac_fp6_mfma_peak": tops_b / FP6_MFMA_PEAK_TOPS,
+            "w4a4_gemm_dequant": {"ms": ms_b, "ms_median_of_tenths": ms_b_median, "ms_min_of_tenths": ms_b_min, "TOPS": tops_b, "frac_fp6_mfma_peak": tops_b / FP6_MFMA_PEAK_TOPS,
                                   "vs_i8_mfma_peak": tops_b / I8_MFMA_PEAK_TOPS,
                                   "min_bytes": bytes_b_min},
         },
