@@ -160,8 +160,8 @@ def main() -> int:
                          "'configs' list) and the W8A8 variant on four of them ('configs_w8a8')")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the path shards over tokens without any "
-              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (token rows are independent, so the path would shard over "
+              "tokens without any exchange); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
